@@ -1,0 +1,56 @@
+"""CPU model of slot placement and the page table: TEST INFRASTRUCTURE, not a product path.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this module.
+
+What it follows.  PagedTensor (Sec. 4.1) gives the type-d tensor of expert l in layer i
+the address  v0 + (i-1) S + (l-1) sigma_d  inside a reusable physical block, and states that
+materialization only updates block contents.  This build replaces the layer term by a page
+table lookup (expert -> staging slot), so the type-d tensor of an expert mapped to slot s
+lives at  base_d + s * sigma_d.  Materializing expert e of layer i into slot s
+
+  * makes slot s hold exactly the original dense bytes of both tensors of e,
+  * sets page_table[i][e] = s,
+  * sets the entry of whichever (layer, expert) owned slot s before to -1,
+  * if e was mapped to another slot before, that slot becomes free,
+  * leaves every other slot byte and page-table entry untouched.
+
+Because decoding is lossless (Sec. 4.2), the slot contents need no codec to define.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+class PagedSlots:
+    def __init__(self, n_layers: int, n_experts: int, n_slots: int, hidden: int, ffn: int,
+                 poison: int = 0x7FC1):
+        self.n13 = 2 * hidden * ffn              # elements of a fused gate/up tensor
+        self.n2 = hidden * ffn                   # elements of a down tensor
+        self.slots13 = np.full((n_slots, self.n13), poison, dtype=np.uint16)
+        self.slots2 = np.full((n_slots, self.n2), poison, dtype=np.uint16)
+        self.page_table = np.full((n_layers, n_experts), -1, dtype=np.int32)
+        self.owner = [None] * n_slots            # (layer, expert) or None
+
+    def materialize(self, layer: int, expert_ids, dst_slots, dense13, dense2):
+        """dense13(e) -> uint16 [n13], dense2(e) -> uint16 [n2] give the original weights."""
+        expert_ids = [int(e) for e in expert_ids]
+        dst_slots = [int(s) for s in dst_slots]
+        assert len(set(expert_ids)) == len(expert_ids)
+        assert len(set(dst_slots)) == len(dst_slots)
+        for e, s in zip(expert_ids, dst_slots):
+            old_slot = int(self.page_table[layer, e])
+            if old_slot >= 0 and old_slot != s:
+                self.owner[old_slot] = None
+            prev = self.owner[s]
+            if prev is not None and prev != (layer, e):
+                self.page_table[prev[0], prev[1]] = -1
+            self.slots13[s] = np.asarray(dense13(e), dtype=np.uint16).reshape(-1)
+            self.slots2[s] = np.asarray(dense2(e), dtype=np.uint16).reshape(-1)
+            self.page_table[layer, e] = s
+            self.owner[s] = (layer, e)
+
+
+def waves(union_ids, n_avail: int):
+    """Cut a sorted routed union into consecutive waves of at most n_avail experts."""
+    ids = sorted(int(e) for e in union_ids)
+    return [ids[i:i + n_avail] for i in range(0, len(ids), n_avail)]

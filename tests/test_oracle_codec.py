@@ -1,0 +1,292 @@
+"""Pins for the codec oracle: things the mathematics or the container rules fix, none of
+which is the oracle's own output fed back to it."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import codec
+from paper_2604_02715_amd import inputs
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def entropy_bits(hist):
+    p = hist[hist > 0] / hist.sum()
+    return float(-(p * np.log2(p)).sum())
+
+
+# ------------------------------------------------------------------ split / join
+def test_split_join_is_a_bit_permutation_of_all_65536_words():
+    w = np.arange(65536, dtype=np.uint16)
+    e, sm = codec.split_bf16(w)
+    assert np.array_equal(codec.join_bf16(e, sm), w)
+    # exponent byte is bits 14..7, sign is bit 7 of sm, mantissa bits 6..0
+    assert e[0x3F80] == 0x7F and sm[0x3F80] == 0x00           # 1.0
+    assert e[0xBF80] == 0x7F and sm[0xBF80] == 0x80           # -1.0
+    assert e[0x7FC1] == 0xFF and sm[0x7FC1] == 0x41           # a NaN payload survives
+    assert e[0x807F] == 0x00 and sm[0x807F] == 0xFF           # negative subnormal
+
+
+# ------------------------------------------------------------------ code lengths
+def brute_force_best_cost(counts, lmax):
+    best = None
+    for lens in itertools.product(range(1, lmax + 1), repeat=len(counts)):
+        if sum(2.0 ** -l for l in lens) <= 1.0 + 1e-12:
+            c = sum(a * b for a, b in zip(counts, lens))
+            best = c if best is None or c < best else best
+    return best
+
+
+@pytest.mark.parametrize("counts,lmax", [
+    ((2, 1, 1), 12), ((5, 1, 1, 1), 2), ((10, 6, 2, 1, 1), 3), ((10, 6, 2, 1, 1), 4),
+    ((1, 1, 1, 1, 1, 1), 3), ((100, 1, 1, 1, 1, 1), 3), ((8, 4, 2, 1, 1), 12),
+    ((13, 8, 5, 3, 2, 1), 3), ((13, 8, 5, 3, 2, 1), 4), ((13, 8, 5, 3, 2, 1), 5),
+])
+def test_length_limited_lengths_are_optimal_by_enumeration(counts, lmax):
+    hist = np.zeros(256, dtype=np.int64)
+    hist[10:10 + len(counts)] = counts
+    lens = codec.code_lengths(hist, lmax)
+    assert lens.max() <= lmax and (lens[hist == 0] == 0).all() and (lens[hist > 0] > 0).all()
+    assert codec.payload_bits(hist, lens) == brute_force_best_cost(counts, lmax)
+
+
+def test_textbook_example_counts_2_1_1():
+    hist = np.zeros(256, dtype=np.int64)
+    hist[[5, 6, 7]] = (2, 1, 1)
+    lens = codec.code_lengths(hist)
+    assert list(lens[[5, 6, 7]]) == [1, 2, 2]
+    codes = codec.canonical_codes(lens)
+    assert list(codes[[5, 6, 7]]) == [0b0, 0b10, 0b11]
+
+
+def test_degenerate_histograms():
+    hist = np.zeros(256, dtype=np.int64)
+    hist[77] = 1000
+    lens = codec.code_lengths(hist)
+    assert lens[77] == 1 and lens.sum() == 1
+    hist = np.full(256, 17, dtype=np.int64)
+    assert (codec.code_lengths(hist, 12) == 8).all()
+    assert (codec.code_lengths(hist, 8) == 8).all()
+    with pytest.raises(ValueError):
+        codec.code_lengths(hist, 7)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_unlimited_huffman_cost_and_kraft_and_monotonicity(seed):
+    rng = np.random.default_rng(seed)
+    k = int(rng.integers(2, 60))
+    hist = np.zeros(256, dtype=np.int64)
+    syms = rng.choice(256, k, replace=False)
+    hist[syms] = rng.integers(1, 5000, k)
+    lens = codec.code_lengths(hist, 32 if k < 33 else 60)       # limit never binds here
+    assert codec.payload_bits(hist, lens) == codec.huffman_cost_unlimited(hist)
+    used = lens > 0
+    assert abs(sum(2.0 ** -int(l) for l in lens[used]) - 1.0) < 1e-12       # Kraft equality
+    order = np.argsort(-hist[used], kind="stable")
+    assert (np.diff(lens[used][order].astype(int)) >= 0).all() or \
+        all(lens[a] <= lens[b] for a in syms for b in syms if hist[a] > hist[b])
+    N, H = hist.sum(), entropy_bits(hist)
+    assert N * H <= codec.payload_bits(hist, lens) < N * (H + 1)
+
+
+def test_limit_binding_costs_more_but_stays_valid():
+    hist = np.zeros(256, dtype=np.int64)
+    hist[:40] = [2 ** min(i, 38) for i in range(40)]            # Fibonacci-like skew
+    lens = codec.code_lengths(hist, 12)
+    assert lens.max() == 12
+    assert abs(sum(2.0 ** -int(l) for l in lens[lens > 0]) - 1.0) < 1e-12
+    assert codec.payload_bits(hist, lens) > codec.huffman_cost_unlimited(hist)
+
+
+def test_canonical_codes_are_prefix_free_and_cover_the_peek_space():
+    rng = np.random.default_rng(3)
+    hist = np.zeros(256, dtype=np.int64)
+    hist[rng.choice(256, 45, replace=False)] = rng.integers(1, 10 ** 6, 45)
+    lens = codec.code_lengths(hist, 12)
+    codes = codec.canonical_codes(lens)
+    words = [format(int(codes[s]), "0%db" % lens[s]) for s in range(256) if lens[s]]
+    for a in words:
+        for b in words:
+            assert a is b or not b.startswith(a)
+    sym, ln = codec._peek_table(lens, 12)
+    assert (sym >= 0).all()                      # complete code: every 12-bit prefix decodes
+    assert sum(2 ** (12 - int(l)) for l in lens[lens > 0]) == 4096
+
+
+# ------------------------------------------------------------------ closed-form entropy
+def test_normal_weights_exponent_entropy_matches_closed_form():
+    """For x ~ N(0, s^2) the exponent byte k has P = erf(2^(k-126)/(s*sqrt2)) -
+    erf(2^(k-127)/(s*sqrt2)); with s = 0.02 the entropy is 2.545 bits."""
+    s = 0.02
+    p = np.array([math.erf(2.0 ** (k - 126) / (s * math.sqrt(2))) -
+                  math.erf(2.0 ** (k - 127) / (s * math.sqrt(2))) for k in range(1, 255)])
+    p = p[p > 0]
+    H_closed = float(-(p * np.log2(p)).sum())
+    assert abs(H_closed - 2.5453) < 2e-3
+    import torch
+    g = torch.Generator().manual_seed(5)
+    w = (torch.randn(1 << 22, generator=g) * s).to(torch.bfloat16)
+    hist = codec.exponent_histogram(inputs.bits_u16(w))
+    assert abs(entropy_bits(hist) - H_closed) < 5e-3
+    lens = codec.code_lengths(hist, 12)
+    avg = codec.payload_bits(hist, lens) / hist.sum()
+    assert H_closed - 5e-3 <= avg < H_closed + 1
+    assert abs(avg - 2.59) < 0.02
+
+
+def test_synthetic_recipe_saves_what_the_paper_reports():
+    """Sec. 4.2 / Tab. 'standalone_decompression': 32.1-32.5 % saved on real checkpoints.
+    The synthetic recipe must land in that neighbourhood before block framing."""
+    w = inputs.weight_matrix(1024, 2048, True, "cpu", "pin")
+    hist = codec.exponent_histogram(inputs.bits_u16(w))
+    lens = codec.code_lengths(hist, 12)
+    bits_per_elem = 8 + codec.payload_bits(hist, lens) / hist.sum()
+    saved = 1 - bits_per_elem / 16
+    assert 0.315 < saved < 0.335
+    # mantissa (+sign) byte is close to uniform: nothing to gain there (App. compressibility)
+    _, sm = codec.split_bf16(inputs.bits_u16(w).reshape(-1))
+    assert entropy_bits(np.bincount(sm, minlength=256)) > 7.95
+
+
+# ------------------------------------------------------------------ hand-built stream
+def handbuilt():
+    n = 64
+    words = np.zeros(n, dtype=np.uint16)
+    for m in range(n):
+        e = 0x78 if m % 4 in (0, 1) else (0x79 if m % 4 == 2 else 0x7A)
+        words[m] = (e << 7) | m
+    blk = np.zeros(4096, dtype=np.uint8)
+    fields = {}
+    for line in open(os.path.join(HERE, "golden", "handbuilt_block.txt")):
+        if line.startswith("#") or ":" not in line:
+            continue
+        k, v = line.split(":", 1)
+        fields[k.strip()] = bytes.fromhex(v.split("+")[0].strip().replace(" ", ""))
+    blk[0:8] = np.frombuffer(fields["n_e0"], dtype=np.uint8)
+    blk[8:8 + len(fields["sub_bits"])] = np.frombuffer(fields["sub_bits"], dtype=np.uint8)
+    blk[136:136 + 64] = np.frombuffer(fields["sm"], dtype=np.uint8)
+    blk[200:200 + len(fields["code"])] = np.frombuffer(fields["code"], dtype=np.uint8)
+    return words, blk
+
+
+def test_handbuilt_block_decodes_bit_by_bit_and_encoder_reproduces_it():
+    words, blk = handbuilt()
+    lens = np.zeros(256, dtype=np.uint8)
+    lens[[0x78, 0x79, 0x7A]] = (1, 2, 2)                     # typed in, not computed
+    e0, out = codec.decode_block_bitwise(blk, lens)
+    assert e0 == 0 and np.array_equal(out, words)
+    e0s, ns, outs = codec.decode_blocks(blk, lens)
+    assert e0s[0] == 0 and ns[0] == 64 and np.array_equal(outs[0], words)
+    blocks, first = codec.encode_tensor(words, codec.code_lengths(codec.exponent_histogram(words)))
+    assert list(first) == [0, 64] and np.array_equal(blocks[0], blk)
+
+
+def test_corrupt_streams_are_rejected():
+    words, blk = handbuilt()
+    lens = np.zeros(256, dtype=np.uint8)
+    lens[[0x78, 0x79, 0x7A]] = (1, 2, 2)
+    bad = blk.copy(); bad[8] = 11                             # sub-stream 0 one bit short
+    with pytest.raises(ValueError):
+        codec.decode_block_bitwise(bad, lens)
+    with pytest.raises(ValueError):
+        codec.decode_blocks(bad, lens)
+    bad = blk.copy(); bad[0] = 63                             # n not a multiple of 64
+    with pytest.raises(ValueError):
+        codec.decode_blocks(bad, lens)
+
+
+# ------------------------------------------------------------------ round trip + container
+def check_container(w, blocks, first, lens, B):
+    N = w.size
+    assert first[0] == 0 and first[-1] == N and (np.diff(first) > 0).all()
+    assert blocks.shape == (len(first) - 1, B)
+    e, _ = codec.split_bf16(w)
+    ebits = lens[e].astype(np.int64)
+    for k in range(blocks.shape[0]):
+        n, e0, sub_bits = codec.block_header(blocks[k])
+        assert e0 == first[k] and n == first[k + 1] - first[k] and n % 64 == 0
+        bits = int(ebits[first[k]:first[k + 1]].sum())
+        assert bits == sub_bits.sum()
+        used = 136 + n + 4 * ((bits + 31) // 32)
+        assert used <= B
+        assert not blocks[k][136 + n + (bits + 7) // 8:].any()        # zero padding
+        tail = blocks[k][136 + n + bits // 8] if bits % 8 else 0
+        assert tail >> (bits % 8) == 0
+        if first[k + 1] < N:                                         # greedy maximality
+            more = int(ebits[first[k]:first[k + 1] + 64].sum())
+            assert 136 + n + 64 + 4 * ((more + 31) // 32) > B
+
+
+@pytest.mark.parametrize("name", list(inputs.adversarial_tensors().keys()))
+@pytest.mark.parametrize("B", [4096, 1024])
+def test_round_trip_adversarial(name, B):
+    w = inputs.adversarial_tensors()[name]
+    lens = codec.code_lengths(codec.exponent_histogram(w), 12)
+    blocks, first = codec.encode_tensor(w, lens, B)
+    check_container(w, blocks, first, lens, B)
+    assert np.array_equal(codec.decode_tensor(blocks, lens, w.size), w)
+    # the literal decoder agrees on the first and last block
+    for k in {0, blocks.shape[0] - 1}:
+        e0, out = codec.decode_block_bitwise(blocks[k], lens)
+        assert np.array_equal(out, w[e0:e0 + out.size])
+
+
+def test_block_with_no_byte_to_spare():
+    """Constant exponent -> 1 bit per element: n + n/8 + 136 = 4096 at n = 3520."""
+    w = np.full(64 * 200, 0x3C55, dtype=np.uint16)
+    lens = codec.code_lengths(codec.exponent_histogram(w))
+    blocks, first = codec.encode_tensor(w, lens, 4096)
+    assert first[1] == 3520 and 136 + 3520 + 3520 // 8 == 4096
+    assert np.array_equal(codec.decode_tensor(blocks, lens, w.size), w)
+
+
+def test_round_trip_layer_pool_tiny_config():
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=3, hidden=64, ffn=128)
+    w13, w2 = inputs.layer_weights(cfg, 0)
+    w13, w2 = inputs.bits_u16(w13), inputs.bits_u16(w2)
+    pool = codec.encode_layer(w13, w2)
+    # blob order: down tensors first, then fused tensors, experts ascending
+    order = [(2, e) for e in range(3)] + [(1, e) for e in range(3)]
+    b = 0
+    for key in order:
+        b0, b1 = pool["tensor_blocks"][key]
+        assert b0 == b and b1 > b0
+        b = b1
+    assert b == pool["blocks"].shape[0]
+    for e in range(3):
+        b0, b1 = pool["tensor_blocks"][(1, e)]
+        got = codec.decode_tensor(pool["blocks"][b0:b1], pool["lens13"], w13[e].size)
+        assert np.array_equal(got, w13[e].reshape(-1))
+        b0, b1 = pool["tensor_blocks"][(2, e)]
+        got = codec.decode_tensor(pool["blocks"][b0:b1], pool["lens2"], w2[e].size)
+        assert np.array_equal(got, w2[e].reshape(-1))
+
+
+def test_compressed_size_including_framing():
+    """4 KiB blocks carry a 136-byte header: about 30 % is saved after framing."""
+    w = inputs.bits_u16(inputs.weight_matrix(1024, 1024, True, "cpu", "ratio")).reshape(-1)
+    lens = codec.code_lengths(codec.exponent_histogram(w))
+    blocks, first = codec.encode_tensor(w, lens, 4096)
+    ratio = blocks.size / (2 * w.size)
+    assert 0.69 < ratio < 0.71
+
+
+def test_table_shapes_reproduce_the_papers_per_gpu_volumes():
+    """Tab. 'standalone_decompression': 1.23 / 0.81 / 0.94 GB decoded per layer per GPU
+    (Mixtral: the 87.5 % GPU share on 2 GPUs; Qwen3-Next on 4; GLM-4.5 on 8)."""
+    c2, c3, c4 = (inputs.CONFIGS[k] for k in ("c2_mixtral", "c3_qwen3next", "c4_glm45"))
+    vol = lambda c: c.n_experts * (c.sigma1 + c.sigma2)
+    assert abs(vol(c2) / 2 * 0.875 / 1e9 - 1.23) < 0.005
+    assert abs(vol(c3) / 4 / 1e9 - 0.81) < 0.005
+    assert abs(vol(c4) / 8 / 1e9 - 0.94) < 0.005
+    for c in (c2, c3, c4):
+        assert c.sigma1 == 2 * c.sigma2 and c.sigma2 % 128 == 0
+
+
+def test_host_tier_split():
+    assert codec.host_tier_blocks(1000, 0.40) == 400
+    assert codec.host_tier_blocks(1001, 0.40) == 401
+    assert codec.host_tier_blocks(1000, 0.0) == 0
