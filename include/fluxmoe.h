@@ -1,0 +1,226 @@
+/*
+ * fluxmoe.h - C ABI of the MI355X expert-materialization library (libfluxmoe.so).
+ *
+ * The library implements the per-layer hot path of expert paging (paper Sec. 3 "Expert
+ * paging"): routed-expert weights live in a losslessly compressed pool (Sec. 4.2
+ * "Compressed GPU backend": Huffman code over the BF16 exponent bits, sign and mantissa
+ * unchanged), are materialized on demand into reusable staging slots (Sec. 4.1
+ * "PagedTensor": reusable physical blocks, contents updated by materialization), and are
+ * then consumed by the expert FFN.  Ordering between the two follows the PagedTensor
+ * synchronization protocol (Alg. 1: write-after-read and read-after-write events).
+ *
+ * Conventions
+ *   - plain C, no exceptions cross the boundary; every call returns a fluxmoe_status
+ *     (0 = OK, negative = error) and leaves a text in fluxmoe_last_error() (thread local).
+ *   - "host" pointers are ordinary process memory, "pinned" is page-locked host memory
+ *     (hipHostMalloc), "device" is HBM of the current HIP device.  All large buffers are
+ *     allocated and owned by the caller and must outlive every enqueued operation; the
+ *     context owns only small host metadata, a small pinned command ring and HIP events.
+ *   - `stream` arguments are hipStream_t values passed as void* (NULL = default stream).
+ *     Calls that take a stream only enqueue work and return.
+ *   - arguments are validated on the host before anything is enqueued; on error nothing
+ *     is enqueued.  Kernels never write outside the bound slot arenas, the page table,
+ *     `out` and the bound workspace, whatever the compressed pool contains.
+ *   - hidden and ffn must be multiples of 8; block_bytes must be 4096.
+ *
+ * Compressed block (block_bytes bytes, independently decodable; this build's container,
+ * the paper prints none):
+ *     +0   u32 n            elements in the block (positive multiple of 64)
+ *     +4   u32 e0           index of the block's first element inside its tensor
+ *     +8   u16 sub_bits[64] bit length of each of the 64 sub-streams
+ *     +136 u8  sm[n]        raw sign|mantissa byte of every element (sign in bit 7)
+ *     +136+n                64 sub-streams back to back, then zero padding
+ *   element m of the block belongs to sub-stream (m >> 3) & 63; stream bit k is bit k & 31
+ *   of little-endian u32 word k >> 5; codes are canonical (sorted by length, then symbol)
+ *   and written first (most significant) code bit first.
+ * Layer blob: blocks of the down tensors (type 2) of experts 0..E-1, then of the fused
+ * gate/up tensors (type 1) of experts 0..E-1; a tensor's blocks are contiguous.
+ */
+#ifndef FLUXMOE_H
+#define FLUXMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fluxmoe_ctx fluxmoe_ctx;
+
+typedef enum {
+    FLUXMOE_OK = 0,
+    FLUXMOE_EINVAL = -1,   /* bad argument */
+    FLUXMOE_ENOMEM = -2,   /* a caller-provided buffer is too small / host allocation failed */
+    FLUXMOE_ECORRUPT = -3, /* compressed pool fails validation */
+    FLUXMOE_ERANGE = -4,   /* layer / expert / slot index out of range */
+    FLUXMOE_EHIP = -5,     /* a HIP runtime call failed (text has the HIP error) */
+    FLUXMOE_ESTATE = -6    /* call made in the wrong state (layer not encoded / not bound) */
+} fluxmoe_status;
+
+/* Homogeneous MoE model (Sec. 3: N layers, L routed experts of one architecture). */
+typedef struct {
+    uint32_t n_layers;     /* N pageable MoE layers */
+    uint32_t n_experts;    /* L routed experts per layer */
+    uint32_t hidden;       /* H */
+    uint32_t ffn;          /* F, per-expert intermediate size */
+    uint32_t block_bytes;  /* compressed block size; 4096 */
+    uint32_t max_code_len; /* Huffman length limit, 8..12 (0 = 12) */
+    uint32_t n_slots;      /* staging budget in experts (slots per arena) */
+    uint32_t flags;        /* reserved, 0 */
+} fluxmoe_desc;
+
+typedef struct {
+    uint64_t sigma1;            /* bytes of one fused gate/up tensor [2][H][F] (type 1) */
+    uint64_t sigma2;            /* bytes of one down tensor [F][H] (type 2); sigma1 = 2 sigma2 */
+    uint64_t slots13_bytes;     /* n_slots * sigma1 */
+    uint64_t slots2_bytes;      /* n_slots * sigma2 */
+    uint64_t page_table_bytes;  /* int32 [n_layers][n_experts] */
+    uint64_t layer_blob_bound;  /* upper bound of one layer's compressed blob */
+    uint64_t pool_workspace_bytes; /* device workspace needed by materialize (tables, commands) */
+} fluxmoe_sizes;
+
+typedef struct {
+    uint64_t n_blocks;          /* blocks in the layer blob */
+    uint64_t payload_bits[2];   /* sum of code lengths over all elements: [0] type 1, [1] type 2 */
+    uint64_t elements[2];       /* elements per type over all experts */
+} fluxmoe_layer_info;
+
+/* Text of the last error on this thread ("" if none).  Never NULL. */
+const char* fluxmoe_last_error(void);
+
+/* Create / destroy a context.  Host only; no HIP call is made until a bind call. */
+int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx);
+int fluxmoe_destroy(fluxmoe_ctx* ctx);
+
+int fluxmoe_query_sizes(const fluxmoe_ctx* ctx, fluxmoe_sizes* out);
+
+/* Device workspace bytes fluxmoe_expert_ffn needs for T tokens with K experts each
+ * (shared_expert != 0 adds the always-on shared expert's rows). */
+uint64_t fluxmoe_ffn_workspace_bytes(const fluxmoe_ctx* ctx, uint32_t T, uint32_t K,
+                                     int shared_expert);
+
+/*
+ * Offline compression of one layer's routed experts (Sec. 4.2: "Huffman-encodes only the
+ * exponent bits offline and leaves the sign and mantissa bits unchanged").  CPU only,
+ * deterministic (independent of n_threads).
+ *   w13  host, BF16 bit patterns [n_experts][2][hidden][ffn]  (gate, then up; y = x W)
+ *   w2   host, BF16 bit patterns [n_experts][ffn][hidden]
+ *   dst  host (may be pinned), receives the layer blob; dst_cap in bytes
+ *   dst_used receives the blob size (a multiple of block_bytes)
+ * One code table per tensor type over all experts of the layer; metadata (code lengths,
+ * block ranges of every tensor) is kept in ctx.  ENOMEM if dst_cap is too small.
+ */
+int fluxmoe_encode_pool(fluxmoe_ctx* ctx, uint32_t layer, const uint16_t* w13,
+                        const uint16_t* w2, void* dst, size_t dst_cap, size_t* dst_used,
+                        int n_threads);
+
+/* Metadata of an encoded layer (host). type: 1 = fused gate/up, 2 = down. */
+int fluxmoe_layer_info_get(const fluxmoe_ctx* ctx, uint32_t layer, fluxmoe_layer_info* out);
+int fluxmoe_code_lengths(const fluxmoe_ctx* ctx, uint32_t layer, int type, uint8_t out_lens[256]);
+int fluxmoe_tensor_blocks(const fluxmoe_ctx* ctx, uint32_t layer, int type, uint32_t expert,
+                          uint64_t* first_block, uint64_t* n_blocks);
+/* first element index of every block of one tensor: out[n_blocks + 1] (last = tensor size) */
+int fluxmoe_tensor_first_elems(const fluxmoe_ctx* ctx, uint32_t layer, int type, uint32_t expert,
+                               uint32_t* out, size_t out_cap);
+
+/*
+ * Bind caller-owned device memory.
+ *   slots13  device, n_slots * sigma1 bytes, 256-byte aligned: type-1 staging slots
+ *   slots2   device, n_slots * sigma2 bytes, 256-byte aligned: type-2 staging slots
+ *   workspace device, 256-byte aligned; at least pool_workspace_bytes; whatever lies
+ *            beyond that is what fluxmoe_expert_ffn may use (see fluxmoe_ffn_workspace_bytes)
+ * The type-d tensor of the expert mapped to slot s lives at slots_d + s * sigma_d (the
+ * PagedTensor address formula of Sec. 4.1 with the layer term replaced by the page table).
+ */
+int fluxmoe_bind_arenas(fluxmoe_ctx* ctx, void* slots13, void* slots2, void* workspace,
+                        size_t workspace_bytes);
+
+/*
+ * Bind one encoded layer's blob, split between the two tiers of Sec. 4.2 ("Memory hierarchy
+ * model"): blocks [0, n_host_blocks) of the blob are read from `host_blocks` (pinned host
+ * memory, block 0 first), blocks [n_host_blocks, n_blocks) from `hbm_blocks` (device; its
+ * first byte is block n_host_blocks).  Either part may be empty (pointer then ignored).
+ * Validates every block header against the encoder's metadata when the blob is host
+ * readable (check_host_copy: optional host pointer to the whole blob, may be NULL) ->
+ * ECORRUPT.  Uploads the layer's decode tables into the workspace (synchronous).
+ */
+int fluxmoe_bind_layer(fluxmoe_ctx* ctx, uint32_t layer, const void* hbm_blocks,
+                       uint64_t n_host_blocks, const void* host_blocks,
+                       const void* check_host_copy);
+
+/* Bind the device staging buffer host-tier blocks are copied into before decoding
+ * (two halves, used alternately by consecutive layers).  Needed only if some layer has
+ * n_host_blocks > 0. */
+int fluxmoe_bind_staging(fluxmoe_ctx* ctx, void* staging, size_t staging_bytes);
+
+/* Enqueue: set every entry of the device page table to -1 and forget all slot ownership. */
+int fluxmoe_reset_page_table(fluxmoe_ctx* ctx, int32_t* page_table, void* stream);
+
+/*
+ * Host-tier fetch (Sec. 4.2 "CPU offload backend": asynchronous DMA from pinned host
+ * memory, overlapped with inference).  Enqueues on copy_stream the hipMemcpyAsync of every
+ * host-tier block the listed experts of `layer` need into the staging half of that layer,
+ * after waiting (on the device) for the last decode that read that half.  A following
+ * fluxmoe_materialize of the same layer and experts waits for these copies.  Optional: if
+ * it was not called, fluxmoe_materialize issues the copies on its own stream.
+ */
+int fluxmoe_prefetch_host(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_ids,
+                          uint32_t n, void* copy_stream);
+
+/*
+ * Materialize experts of one layer into staging slots (Sec. 3: "materialized only when
+ * their layer is scheduled"; Alg. 1 MaterializeLayer).
+ *   expert_ids host, n distinct ids in [0, n_experts)
+ *   dst_slots  host, n distinct slots in [0, n_slots)
+ *   page_table device int32 [n_layers][n_experts]; the same table on every call
+ * Enqueued on `stream`: wait for the last expert-FFN call that read any of the target
+ * slots (write-after-read), [wait for the layer's host-tier copies], decode + paged
+ * scatter, page-table update, record the layer's load event.  After that event, for each
+ * i: slot dst_slots[i] holds exactly the original bytes of both tensors of expert_ids[i],
+ * page_table[layer][expert_ids[i]] = dst_slots[i], the entry of whichever (layer, expert)
+ * owned that slot before is -1; nothing else changes.  n = 0 is valid and enqueues nothing.
+ */
+int fluxmoe_materialize(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_ids,
+                        uint32_t n, int32_t* page_table, const int32_t* dst_slots,
+                        void* stream);
+
+/*
+ * Release experts of one layer (Sec. 3: "After the MoE block of layer i-1 completes, the
+ * proxy releases E_{i-1}"): enqueue page_table[layer][e] = -1 for the listed experts that are
+ * mapped; their slots become free for reuse (a later materialize into them still waits for
+ * the FFN that last read them).  expert_ids NULL with n = 0 releases every expert of the
+ * layer.  Slot contents are not touched.
+ */
+int fluxmoe_release(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_ids, uint32_t n,
+                    int32_t* page_table, void* stream);
+
+/* fluxmoe_expert_ffn flags */
+#define FLUXMOE_FFN_ACCUMULATE 1u    /* out += result instead of out = result */
+#define FLUXMOE_FFN_SKIP_UNMAPPED 2u /* ignore (token, k) pairs whose expert is not mapped
+                                        (a wave of a slot budget smaller than the union);
+                                        without it such a pair sets the device error flag */
+
+/*
+ * Routed SwiGLU expert FFN over the materialized slots (Alg. 1 ForwardPass: wait for the
+ * layer's load event, launch, record the inference event).
+ *   tokens   device BF16 [T][hidden]
+ *   topk_ids device int32 [T][K], topk_w device float [T][K]
+ *   page_table device int32 [n_layers][n_experts] (expert -> slot, -1 = not resident)
+ *   out      device float [T][hidden]
+ * out_t = sum_k topk_w[t][k] * ( (silu(x_t W1_e) * (x_t W3_e)) W2_e ),  e = topk_ids[t][k];
+ * BF16 inputs, FP32 accumulation, the SwiGLU product rounded to BF16 before the second
+ * product.  Deterministic (fixed summation order).  T = 0 is valid.
+ */
+int fluxmoe_expert_ffn(fluxmoe_ctx* ctx, uint32_t layer, const uint16_t* tokens, uint32_t T,
+                       const int32_t* topk_ids, const float* topk_w, uint32_t K,
+                       const int32_t* page_table, float* out, uint32_t flags, void* stream);
+
+/* Synchronous: read and clear the device error word (0 = none; bit 0 a block failed
+ * validation during decode and was skipped, bit 1 an unmapped expert was routed to). */
+int fluxmoe_device_errors(fluxmoe_ctx* ctx, uint32_t* out_flags);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLUXMOE_H */

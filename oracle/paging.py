@@ -49,6 +49,16 @@ class PagedSlots:
             self.page_table[layer, e] = s
             self.owner[s] = (layer, e)
 
+    def release(self, layer: int, expert_ids=None):
+        """Sec. 3: after a layer's MoE block the proxy releases its experts: the mappings go,
+        the slot bytes stay."""
+        ids = range(self.page_table.shape[1]) if expert_ids is None else expert_ids
+        for e in ids:
+            s = int(self.page_table[layer, int(e)])
+            if s >= 0:
+                self.page_table[layer, int(e)] = -1
+                self.owner[s] = None
+
 
 def waves(union_ids, n_avail: int):
     """Cut a sorted routed union into consecutive waves of at most n_avail experts."""

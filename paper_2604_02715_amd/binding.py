@@ -1,0 +1,200 @@
+"""ctypes binding of libfluxmoe.so: argument marshalling only, same names as include/fluxmoe.h.
+
+Every step of the path runs inside the library's HIP kernels; there is no fallback.  If the
+library has not been built, loading raises (build it with python -m paper_2604_02715_amd.build).
+Pointers are passed as integers (torch's tensor.data_ptr(), numpy's arr.ctypes.data).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfluxmoe.so")
+_lib = None
+
+FFN_ACCUMULATE = 1
+FFN_SKIP_UNMAPPED = 2
+
+STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ECORRUPT", -4: "ERANGE", -5: "EHIP", -6: "ESTATE"}
+
+
+class FluxmoeError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("fluxmoe %s (%d): %s" % (STATUS.get(status, "?"), status, text))
+        self.status = status
+
+
+class Desc(C.Structure):
+    _fields_ = [(n, C.c_uint32) for n in ("n_layers", "n_experts", "hidden", "ffn", "block_bytes",
+                                          "max_code_len", "n_slots", "flags")]
+
+
+class Sizes(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("sigma1", "sigma2", "slots13_bytes", "slots2_bytes",
+                                          "page_table_bytes", "layer_blob_bound",
+                                          "pool_workspace_bytes")]
+
+
+class LayerInfo(C.Structure):
+    _fields_ = [("n_blocks", C.c_uint64), ("payload_bits", C.c_uint64 * 2),
+                ("elements", C.c_uint64 * 2)]
+
+
+EXPORTS = {
+    "fluxmoe_last_error": (C.c_char_p, []),
+    "fluxmoe_create": (C.c_int, [C.POINTER(Desc), C.POINTER(C.c_void_p)]),
+    "fluxmoe_destroy": (C.c_int, [C.c_void_p]),
+    "fluxmoe_query_sizes": (C.c_int, [C.c_void_p, C.POINTER(Sizes)]),
+    "fluxmoe_ffn_workspace_bytes": (C.c_uint64, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_int]),
+    "fluxmoe_encode_pool": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_size_t, C.POINTER(C.c_size_t), C.c_int]),
+    "fluxmoe_layer_info_get": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(LayerInfo)]),
+    "fluxmoe_code_lengths": (C.c_int, [C.c_void_p, C.c_uint32, C.c_int, C.c_void_p]),
+    "fluxmoe_tensor_blocks": (C.c_int, [C.c_void_p, C.c_uint32, C.c_int, C.c_uint32,
+                                        C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]),
+    "fluxmoe_tensor_first_elems": (C.c_int, [C.c_void_p, C.c_uint32, C.c_int, C.c_uint32,
+                                             C.c_void_p, C.c_size_t]),
+    "fluxmoe_bind_arenas": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
+    "fluxmoe_bind_layer": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p,
+                                     C.c_void_p]),
+    "fluxmoe_bind_staging": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t]),
+    "fluxmoe_reset_page_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
+    "fluxmoe_prefetch_host": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p]),
+    "fluxmoe_materialize": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
+                                      C.c_void_p, C.c_void_p]),
+    "fluxmoe_release": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]),
+    "fluxmoe_expert_ffn": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
+                                     C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
+                                     C.c_void_p]),
+    "fluxmoe_device_errors": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
+}
+
+
+def lib():
+    """Load libfluxmoe.so (once).  Raises if it is missing: there is no other code path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                _LIB_PATH + " is missing: run `python -m paper_2604_02715_amd.build` "
+                "(or __graft_entry__.build()); this package has no non-HIP code path")
+        handle = C.CDLL(_LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise FluxmoeError(rc, lib().fluxmoe_last_error().decode())
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def fluxmoe_create(n_layers, n_experts, hidden, ffn, n_slots, block_bytes=4096, max_code_len=12):
+    d = Desc(n_layers, n_experts, hidden, ffn, block_bytes, max_code_len, n_slots, 0)
+    h = C.c_void_p()
+    _check(lib().fluxmoe_create(C.byref(d), C.byref(h)))
+    return h
+
+
+def fluxmoe_destroy(ctx):
+    _check(lib().fluxmoe_destroy(ctx))
+
+
+def fluxmoe_query_sizes(ctx) -> Sizes:
+    s = Sizes()
+    _check(lib().fluxmoe_query_sizes(ctx, C.byref(s)))
+    return s
+
+
+def fluxmoe_ffn_workspace_bytes(ctx, T, K, shared_expert=False) -> int:
+    return int(lib().fluxmoe_ffn_workspace_bytes(ctx, T, K, int(shared_expert)))
+
+
+def fluxmoe_encode_pool(ctx, layer, w13_ptr, w2_ptr, dst_ptr, dst_cap, n_threads=8) -> int:
+    used = C.c_size_t(0)
+    _check(lib().fluxmoe_encode_pool(ctx, layer, w13_ptr, w2_ptr, dst_ptr, dst_cap, C.byref(used),
+                                     n_threads))
+    return int(used.value)
+
+
+def fluxmoe_layer_info_get(ctx, layer) -> LayerInfo:
+    info = LayerInfo()
+    _check(lib().fluxmoe_layer_info_get(ctx, layer, C.byref(info)))
+    return info
+
+
+def fluxmoe_code_lengths(ctx, layer, type_) -> np.ndarray:
+    out = np.zeros(256, dtype=np.uint8)
+    _check(lib().fluxmoe_code_lengths(ctx, layer, type_, out.ctypes.data))
+    return out
+
+
+def fluxmoe_tensor_blocks(ctx, layer, type_, expert):
+    a, b = C.c_uint64(), C.c_uint64()
+    _check(lib().fluxmoe_tensor_blocks(ctx, layer, type_, expert, C.byref(a), C.byref(b)))
+    return int(a.value), int(b.value)
+
+
+def fluxmoe_tensor_first_elems(ctx, layer, type_, expert) -> np.ndarray:
+    _, nb = fluxmoe_tensor_blocks(ctx, layer, type_, expert)
+    out = np.zeros(nb + 1, dtype=np.uint32)
+    _check(lib().fluxmoe_tensor_first_elems(ctx, layer, type_, expert, out.ctypes.data, out.size))
+    return out
+
+
+def fluxmoe_bind_arenas(ctx, slots13_ptr, slots2_ptr, workspace_ptr, workspace_bytes):
+    _check(lib().fluxmoe_bind_arenas(ctx, slots13_ptr, slots2_ptr, workspace_ptr, workspace_bytes))
+
+
+def fluxmoe_bind_layer(ctx, layer, hbm_ptr, n_host_blocks=0, host_ptr=None, check_host_copy_ptr=None):
+    _check(lib().fluxmoe_bind_layer(ctx, layer, hbm_ptr, n_host_blocks, host_ptr, check_host_copy_ptr))
+
+
+def fluxmoe_bind_staging(ctx, staging_ptr, staging_bytes):
+    _check(lib().fluxmoe_bind_staging(ctx, staging_ptr, staging_bytes))
+
+
+def fluxmoe_reset_page_table(ctx, page_table_ptr, stream=None):
+    _check(lib().fluxmoe_reset_page_table(ctx, page_table_ptr, stream))
+
+
+def fluxmoe_prefetch_host(ctx, layer, expert_ids, copy_stream=None):
+    ids = _i32(expert_ids)
+    _check(lib().fluxmoe_prefetch_host(ctx, layer, ids.ctypes.data, ids.size, copy_stream))
+
+
+def fluxmoe_materialize(ctx, layer, expert_ids, page_table_ptr, dst_slots, stream=None):
+    ids, slots = _i32(expert_ids), _i32(dst_slots)
+    if ids.size != slots.size:
+        raise ValueError("expert_ids and dst_slots differ in length")
+    _check(lib().fluxmoe_materialize(ctx, layer, ids.ctypes.data, ids.size, page_table_ptr,
+                                     slots.ctypes.data, stream))
+
+
+def fluxmoe_release(ctx, layer, expert_ids, page_table_ptr, stream=None):
+    if expert_ids is None:
+        _check(lib().fluxmoe_release(ctx, layer, None, 0, page_table_ptr, stream))
+    else:
+        ids = _i32(expert_ids)
+        _check(lib().fluxmoe_release(ctx, layer, ids.ctypes.data, ids.size, page_table_ptr, stream))
+
+
+def fluxmoe_expert_ffn(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K, page_table_ptr,
+                       out_ptr, flags=0, stream=None):
+    _check(lib().fluxmoe_expert_ffn(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K,
+                                    page_table_ptr, out_ptr, flags, stream))
+
+
+def fluxmoe_device_errors(ctx) -> int:
+    f = C.c_uint32(0)
+    _check(lib().fluxmoe_device_errors(ctx, C.byref(f)))
+    return int(f.value)

@@ -1,0 +1,371 @@
+// Routed SwiGLU expert FFN over page-table addressed slots (gfx950, BF16 MFMA, FP32 acc).
+//
+// The paper runs an unchanged fused-MoE kernel on the materialized tensors (Sec. 5; tensor
+// types of Sec. 4.1 "Formal model": fused gate/up [2][H][F] and down [F][H]); it gives no
+// kernel design, so this one is built for decode-shaped batches on MI355X, where every
+// expert sees few tokens and the FFN is bound by streaming the expert's weights once:
+//
+//   route_sort   one workgroup: counting sort of the (token, k) pairs by expert, skipping
+//                pairs whose expert has no slot; emits row tiles (expert, first row)
+//   gemm1        per (row tile, 128-column strip): a = X W1, b = X W3 with
+//                v_mfma_f32_16x16x32_bf16, h = silu(a) * b rounded to BF16
+//   gemm2        per (row tile, 128-column strip, K split): y = h W2, FP32 partial sums
+//   combine      out[t] = sum_k gate[t][k] * sum_splits y[pos(t,k)]   (fixed order)
+//
+// Weights stay row-major [K][N] in the slots (placement is bit-exact by contract), while
+// MFMA wants 8 consecutive k per lane.  Each lane therefore loads 8 rows x 16 bytes (8
+// columns) straight from HBM, fully coalesced along N, and transposes its 8x8 tile in
+// registers with v_perm_b32; MFMA number c of a step uses column c of every lane's tile,
+// so output column j of that MFMA is column 8 * j + c of the strip.  No LDS is involved
+// and every weight byte is read exactly once per row tile.
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace fluxmoe {
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+union Frag {
+    uint4 u;
+    bf16x8 v;
+};
+
+constexpr int kStrip = 128;        // output columns per wavefront
+constexpr int kChunk = 32;         // k per MFMA step
+
+// ------------------------------------------------------------------ routing / grouping
+__global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
+    extern __shared__ int32_t sh[];          // count[E], cursor[E], scan scratch[1024]
+    int32_t* count = sh;
+    int32_t* cursor = sh + a.E;
+    int32_t* scratch = sh + 2 * a.E;
+    __shared__ int32_t carry, tile_carry;
+    const int tid = threadIdx.x;
+    const uint32_t pairs = a.T * a.K;
+    for (uint32_t e = tid; e < a.E; e += 1024) count[e] = 0;
+    if (tid == 0) { carry = 0; tile_carry = 0; }
+    __syncthreads();
+    for (uint32_t p = tid; p < pairs; p += 1024) {
+        const int32_t e = a.topk_ids[p];
+        bool keep = false;
+        if (e < 0 || uint32_t(e) >= a.E) {
+            atomicOr(a.error_word, 2u);
+        } else if (a.page_table[e] < 0) {
+            if (!(a.flags & 2u)) atomicOr(a.error_word, 2u);
+        } else {
+            keep = true;
+        }
+        if (keep) atomicAdd(&count[e], 1);
+    }
+    __syncthreads();
+    // exclusive scans over experts (rows and tiles), 1024 experts per round
+    for (uint32_t base = 0; base < a.E; base += 1024) {
+        const uint32_t e = base + tid;
+        const int32_t c = (e < a.E) ? count[e] : 0;
+        const int32_t t = (c + int32_t(a.m_tile) - 1) / int32_t(a.m_tile);
+        // rows
+        scratch[tid] = c;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {
+            const int32_t v = (tid >= d) ? scratch[tid - d] : 0;
+            __syncthreads();
+            scratch[tid] += v;
+            __syncthreads();
+        }
+        const int32_t row_excl = scratch[tid] - c + carry;
+        const int32_t row_total = scratch[1023];
+        __syncthreads();
+        // tiles
+        scratch[tid] = t;
+        __syncthreads();
+        for (int d = 1; d < 1024; d <<= 1) {
+            const int32_t v = (tid >= d) ? scratch[tid - d] : 0;
+            __syncthreads();
+            scratch[tid] += v;
+            __syncthreads();
+        }
+        const int32_t tile_excl = scratch[tid] - t + tile_carry;
+        const int32_t tile_total = scratch[1023];
+        __syncthreads();
+        if (e < a.E) {
+            a.expert_offset[e] = row_excl;
+            a.expert_count[e] = c;
+            cursor[e] = row_excl;
+            for (int32_t i = 0; i < t; ++i) {
+                if (uint32_t(tile_excl + i) < a.tiles_cap) {
+                    a.tile_expert[tile_excl + i] = int32_t(e);
+                    a.tile_row0[tile_excl + i] = row_excl + i * int32_t(a.m_tile);
+                }
+            }
+        }
+        if (tid == 0) { carry += row_total; tile_carry += tile_total; }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        a.expert_offset[a.E] = carry;
+        a.n_tiles[0] = min(tile_carry, int32_t(a.tiles_cap));
+    }
+    __syncthreads();
+    for (uint32_t p = tid; p < pairs; p += 1024) {
+        const int32_t e = a.topk_ids[p];
+        int32_t pos = -1;
+        if (e >= 0 && uint32_t(e) < a.E && a.page_table[e] >= 0) {
+            pos = atomicAdd(&cursor[e], 1);
+            a.sorted_pair[pos] = int32_t(p);
+        }
+        a.pair_pos[p] = pos;
+    }
+}
+
+// ------------------------------------------------------------------ strip GEMM core
+__device__ __forceinline__ uint32_t comp(const uint4& v, int i) {
+    return i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w));
+}
+
+template <int MI, int NMAT>
+struct StripGemm {
+    f32x4 acc[MI][8][NMAT];
+    uint4 bv[NMAT][8];
+    uint4 av[MI];
+
+    __device__ __forceinline__ void zero() {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+#pragma unroll
+                for (int m = 0; m < NMAT; ++m) acc[mi][c][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // lane's rows k0..k0+7 of the B strip (its 8 columns must exist) and its A fragments
+    // (a lane's A row is independent of its B columns); k_ok = k0 inside the k range
+    __device__ __forceinline__ void load(const uint16_t* const (&arow)[MI], const uint16_t* bcol,
+                                         size_t ldb, size_t mat_stride, uint32_t k0, bool k_ok,
+                                         bool col_ok) {
+        const bool ok = k_ok && col_ok;
+        const uint4 z = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+            for (int r = 0; r < 8; ++r)
+                bv[m][r] = ok ? load_stream16(bcol + m * mat_stride + size_t(k0 + r) * ldb) : z;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+            av[mi] = k_ok ? *reinterpret_cast<const uint4*>(arow[mi] + k0) : z;
+    }
+
+    __device__ __forceinline__ void mma(const uint4 (&b)[NMAT][8], const uint4 (&a)[MI]) {
+#pragma unroll
+        for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                Frag f;
+                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+                f.u.x = __builtin_amdgcn_perm(comp(b[m][1], c >> 1), comp(b[m][0], c >> 1), sel);
+                f.u.y = __builtin_amdgcn_perm(comp(b[m][3], c >> 1), comp(b[m][2], c >> 1), sel);
+                f.u.z = __builtin_amdgcn_perm(comp(b[m][5], c >> 1), comp(b[m][4], c >> 1), sel);
+                f.u.w = __builtin_amdgcn_perm(comp(b[m][7], c >> 1), comp(b[m][6], c >> 1), sel);
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi) {
+                    Frag fa;
+                    fa.u = a[mi];
+                    acc[mi][c][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v, f.v, acc[mi][c][m], 0, 0, 0);
+                }
+            }
+    }
+
+    // C = A[rows][k_begin:k_end] * B[k_begin:k_end][strip]; k range multiple of 8
+    __device__ __forceinline__ void run(const uint16_t* const (&arow)[MI], const uint16_t* bcol,
+                                        size_t ldb, size_t mat_stride, uint32_t k_begin,
+                                        uint32_t k_end, bool col_ok, int lane) {
+        zero();
+        const uint32_t kg = 8u * (uint32_t(lane) >> 4);
+        uint32_t k0 = k_begin + kg;
+        load(arow, bcol, ldb, mat_stride, k0, k0 < k_end, col_ok);
+        for (uint32_t kc = k_begin; kc < k_end; kc += kChunk) {
+            uint4 bcur[NMAT][8];
+            uint4 acur[MI];
+#pragma unroll
+            for (int m = 0; m < NMAT; ++m)
+#pragma unroll
+                for (int r = 0; r < 8; ++r) bcur[m][r] = bv[m][r];
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) acur[mi] = av[mi];
+            const uint32_t kn = kc + kChunk + kg;
+            if (kc + kChunk < k_end) load(arow, bcol, ldb, mat_stride, kn, kn < k_end, col_ok);
+            mma(bcur, acur);
+        }
+    }
+};
+
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+struct TileInfo {
+    int32_t expert, row0, rows, slot;
+};
+
+__device__ __forceinline__ bool tile_info(const FfnArgs& a, uint32_t tile, TileInfo& t) {
+    if (int32_t(tile) >= a.n_tiles[0]) return false;
+    t.expert = a.tile_expert[tile];
+    t.row0 = a.tile_row0[tile];
+    const int32_t end = a.expert_offset[t.expert] + a.expert_count[t.expert];
+    t.rows = min(int32_t(a.m_tile), end - t.row0);
+    t.slot = a.page_table[t.expert];
+    return t.rows > 0 && t.slot >= 0;
+}
+
+// h[row][n] = bf16( silu(x W1) * (x W3) )
+template <int MI>
+__global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
+    TileInfo t;
+    if (!tile_info(a, blockIdx.y, t)) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const uint32_t strip = blockIdx.x * 4 + wave;
+    const uint32_t n0 = strip * kStrip + 8u * (lane & 15);
+    if (strip * kStrip >= a.F) return;
+    const bool col_ok = n0 < a.F;
+
+    const uint16_t* arow[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        const int32_t r = min(mi * 16 + (lane & 15), t.rows - 1);
+        const int32_t pair = a.sorted_pair[t.row0 + r];
+        const uint32_t tok = uint32_t(pair) / a.K;
+        arow[mi] = a.tokens + size_t(tok) * a.H;
+    }
+    const size_t mat = size_t(a.H) * a.F;
+    const uint16_t* w13 = a.slots13 + size_t(t.slot) * 2 * mat;
+
+    StripGemm<MI, 2> g;
+    g.run(arow, w13 + n0, a.F, mat, 0, a.H, col_ok, lane);
+
+    if (!col_ok) return;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int32_t row = mi * 16 + 4 * (lane >> 4) + r;
+            if (row >= t.rows) continue;
+            uint32_t hb[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const float ga = g.acc[mi][c][0][r];
+                const float up = g.acc[mi][c][1][r];
+                const float h = ga / (1.0f + __expf(-ga)) * up;
+                hb[c] = f32_to_bf16_rne(h);
+            }
+            uint4 o;
+            o.x = hb[0] | (hb[1] << 16);
+            o.y = hb[2] | (hb[3] << 16);
+            o.z = hb[4] | (hb[5] << 16);
+            o.w = hb[6] | (hb[7] << 16);
+            *reinterpret_cast<uint4*>(a.hbuf + size_t(t.row0 + row) * a.F + n0) = o;
+        }
+}
+
+// y[split][row][n] = h[row][k range] W2[k range][n]
+template <int MI>
+__global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
+    TileInfo t;
+    if (!tile_info(a, blockIdx.y, t)) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const uint32_t strip = blockIdx.x * 4 + wave;
+    const uint32_t n0 = strip * kStrip + 8u * (lane & 15);
+    if (strip * kStrip >= a.H) return;
+    const bool col_ok = n0 < a.H;
+    const uint32_t split = blockIdx.z;
+    const uint32_t k_per = ((a.F + a.ksplit - 1) / a.ksplit + kChunk - 1) / kChunk * kChunk;
+    const uint32_t k_begin = min(a.F, split * k_per);
+    const uint32_t k_end = min(a.F, k_begin + k_per);
+
+    const uint16_t* arow[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi) {
+        const int32_t r = min(mi * 16 + (lane & 15), t.rows - 1);
+        arow[mi] = a.hbuf + size_t(t.row0 + r) * a.F;
+    }
+    const uint16_t* w2 = a.slots2 + size_t(t.slot) * a.F * a.H;
+
+    StripGemm<MI, 1> g;
+    g.run(arow, w2 + n0, a.H, 0, k_begin, k_end, col_ok, lane);
+
+    if (!col_ok) return;
+    float* y = a.ybuf + size_t(split) * a.pairs_cap * a.H;
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int32_t row = mi * 16 + 4 * (lane >> 4) + r;
+            if (row >= t.rows) continue;
+            float4 lo = make_float4(g.acc[mi][0][0][r], g.acc[mi][1][0][r], g.acc[mi][2][0][r],
+                                    g.acc[mi][3][0][r]);
+            float4 hi = make_float4(g.acc[mi][4][0][r], g.acc[mi][5][0][r], g.acc[mi][6][0][r],
+                                    g.acc[mi][7][0][r]);
+            float4* dst = reinterpret_cast<float4*>(y + size_t(t.row0 + row) * a.H + n0);
+            dst[0] = lo;
+            dst[1] = hi;
+        }
+}
+
+// out[t][:] (+)= sum_k gate * sum_split y
+__global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
+    const uint32_t tok = blockIdx.y;
+    const uint32_t h = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (h >= a.H) return;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    float* o = a.out + size_t(tok) * a.H + h;
+    if (a.flags & 1u) s = *reinterpret_cast<const float4*>(o);
+    for (uint32_t k = 0; k < a.K; ++k) {
+        const int32_t pos = a.pair_pos[tok * a.K + k];
+        if (pos < 0) continue;
+        const float gate = a.topk_w[tok * a.K + k];
+        float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t sp = 0; sp < a.ksplit; ++sp) {
+            const float4 v = *reinterpret_cast<const float4*>(
+                a.ybuf + (size_t(sp) * a.pairs_cap + pos) * a.H + h);
+            y.x += v.x; y.y += v.y; y.z += v.z; y.w += v.w;
+        }
+        s.x += gate * y.x; s.y += gate * y.y; s.z += gate * y.z; s.w += gate * y.w;
+    }
+    *reinterpret_cast<float4*>(o) = s;
+}
+
+}  // namespace
+
+hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream) {
+    (void)n_cus;
+    if (a.T == 0) return hipSuccess;
+    const size_t sh = (2 * size_t(a.E) + 1024) * sizeof(int32_t);
+    hipLaunchKernelGGL(route_sort_kernel, dim3(1), dim3(1024), sh, stream, a);
+    const uint32_t strips1 = (a.F + kStrip - 1) / kStrip;
+    const uint32_t strips2 = (a.H + kStrip - 1) / kStrip;
+    const dim3 g1((strips1 + 3) / 4, a.tiles_cap, 1);
+    const dim3 g2((strips2 + 3) / 4, a.tiles_cap, a.ksplit);
+    switch (a.m_tile) {
+        case 16:
+            hipLaunchKernelGGL(gemm1_swiglu_kernel<1>, g1, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(gemm2_kernel<1>, g2, dim3(256), 0, stream, a);
+            break;
+        case 32:
+            hipLaunchKernelGGL(gemm1_swiglu_kernel<2>, g1, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL(gemm2_kernel<2>, g2, dim3(256), 0, stream, a);
+            break;
+        default:
+            return hipErrorInvalidValue;
+    }
+    const dim3 gc((a.H / 4 + 255) / 256, a.T, 1);
+    hipLaunchKernelGGL(combine_kernel, gc, dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace fluxmoe

@@ -1,0 +1,797 @@
+// Host side of libfluxmoe.so: context, offline encode driver, tier binding, the
+// materialize / expert-FFN enqueue paths and the event protocol between them.
+//
+// Event protocol = PagedTensor synchronization (paper Alg. 1), generalised from the two
+// reusable layer blocks to individual staging slots: a materialize waits for the inference
+// event of every layer whose FFN last read one of its target slots (write-after-read); an
+// FFN call waits for its layer's load event (read-after-write) and records the layer's
+// inference event.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <array>
+#include <atomic>
+#include <cstring>
+#include <new>
+#include <thread>
+
+#include "fluxmoe_internal.h"
+
+namespace fluxmoe {
+
+static thread_local char g_err[512] = "";
+
+int set_error(int status, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return status;
+}
+
+}  // namespace fluxmoe
+
+using namespace fluxmoe;
+
+#define HIPCHECK(call)                                                                  \
+    do {                                                                                \
+        hipError_t e_ = (call);                                                         \
+        if (e_ != hipSuccess)                                                           \
+            return set_error(FLUXMOE_EHIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+namespace {
+constexpr int kRing = 4;
+constexpr uint32_t kLutBytes = kLutEntries * 4;
+
+struct StageState {
+    bool valid = false;
+    std::vector<int64_t> off[2];   // per expert: byte offset of the tensor's host part in the half
+};
+
+struct FfnPlan {
+    uint32_t m_tile, ksplit, pairs_cap, tiles_cap;
+    uint64_t bytes;
+    uint64_t off_count, off_offset, off_sorted, off_pos, off_tile_e, off_tile_r, off_ntiles, off_h, off_y;
+};
+
+inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+}  // namespace
+
+struct fluxmoe_ctx {
+    fluxmoe_desc d;
+    uint64_t elems13 = 0, elems2 = 0;
+    std::vector<LayerMeta> layers;
+    // arenas
+    uint8_t* slots13 = nullptr;
+    uint8_t* slots2 = nullptr;
+    uint8_t* ws = nullptr;
+    size_t ws_bytes = 0;
+    bool arenas_bound = false;
+    int n_cus = 256;
+    // pool workspace layout
+    uint64_t lut_off = 0, cmd_off = 0, err_off = 0, pool_ws_bytes = 0;
+    uint32_t max_jobs = 0, max_upd = 0, cmd_bytes = 0;
+    // command ring (pinned host mirror of the device command buffers)
+    uint8_t* pinned_cmd = nullptr;
+    hipEvent_t ring_ev[kRing] = {};
+    bool ring_used[kRing] = {};
+    int ring_next = 0;
+    // page-table mirror and slot ownership
+    std::vector<int32_t> pt;
+    std::vector<int64_t> slot_owner;      // layer * E + expert, or -1
+    // Alg. 1 state
+    std::vector<hipEvent_t> ev_load, ev_infer;
+    std::vector<uint8_t> load_valid, infer_valid;
+    std::vector<int32_t> slot_last_reader; // layer whose FFN last read the slot, or -1
+    bool events_ready = false;
+    // host-tier staging
+    uint8_t* staging = nullptr;
+    size_t staging_bytes = 0;
+    std::vector<StageState> stage;
+    std::vector<hipEvent_t> ev_copied;
+    hipEvent_t ev_half_done[2] = {};
+    bool half_done_valid[2] = {false, false};
+};
+
+namespace {
+
+void compute_layout(fluxmoe_ctx* c) {
+    const uint64_t E = c->d.n_experts;
+    c->max_jobs = uint32_t(2 * E + 2);
+    c->max_upd = uint32_t(2 * E + 2);
+    c->cmd_bytes = uint32_t(align_up(sizeof(DecodeCmd) + 2ull * c->max_jobs * sizeof(DecodeJob) +
+                                     c->max_upd * 8ull, 256));
+    c->lut_off = 0;
+    c->cmd_off = align_up(uint64_t(c->d.n_layers) * 2 * kLutBytes, 256);
+    c->err_off = c->cmd_off + uint64_t(kRing) * c->cmd_bytes;
+    c->pool_ws_bytes = align_up(c->err_off + 256, 4096);
+}
+
+FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
+    FfnPlan p{};
+    const uint64_t E = c->d.n_experts, H = c->d.hidden, F = c->d.ffn;
+    const uint64_t pairs = uint64_t(T) * K;
+    const uint64_t groups = std::max<uint64_t>(1, std::min<uint64_t>(E, pairs));
+    const uint64_t avg = (pairs + groups - 1) / groups;
+    p.m_tile = avg > 16 ? 32 : 16;
+    p.pairs_cap = uint32_t(std::max<uint64_t>(pairs, 1));
+    p.tiles_cap = uint32_t(pairs / p.m_tile + groups + 1);
+    // split K of the second product until about 8 wavefronts per CU have work
+    const uint64_t strips2 = (H + 127) / 128;
+    const uint64_t est_tiles = std::max<uint64_t>(1, std::max<uint64_t>(pairs / p.m_tile, std::min(groups, pairs)));
+    const uint64_t jobs = strips2 * est_tiles;
+    uint64_t ks = (2048 + jobs - 1) / jobs;
+    ks = std::min<uint64_t>(ks, 8);
+    ks = std::min<uint64_t>(ks, std::max<uint64_t>(1, F / 256));
+    p.ksplit = uint32_t(std::max<uint64_t>(ks, 1));
+    uint64_t o = 0;
+    auto take = [&](uint64_t bytes) { uint64_t at = o; o = align_up(o + bytes, 256); return at; };
+    p.off_count = take((E + 1) * 4);
+    p.off_offset = take((E + 2) * 4);
+    p.off_sorted = take(uint64_t(p.pairs_cap) * 4);
+    p.off_pos = take(uint64_t(p.pairs_cap) * 4);
+    p.off_tile_e = take(uint64_t(p.tiles_cap) * 4);
+    p.off_tile_r = take(uint64_t(p.tiles_cap) * 4);
+    p.off_ntiles = take(4);
+    p.off_h = take(uint64_t(p.pairs_cap) * F * 2);
+    p.off_y = take(uint64_t(p.ksplit) * p.pairs_cap * H * 4);
+    p.bytes = o;
+    return p;
+}
+
+void build_lut(const uint8_t lens[256], uint32_t* lut) {
+    uint16_t codes[256];
+    canonical_codes(lens, codes);
+    int fallback = -1;
+    for (int s = 0; s < 256; ++s)
+        if (lens[s]) { fallback = s; break; }
+    const uint32_t fill = fallback < 0 ? 1u : ((uint32_t(fallback) << 23) | 1u);
+    for (uint32_t i = 0; i < kLutEntries; ++i) lut[i] = fill;
+    for (int s = 0; s < 256; ++s) {
+        const uint32_t L = lens[s];
+        if (!L || L > kLutBits) continue;
+        uint32_t rev = 0;   // first code bit in bit 0: that is how the stream is peeked
+        for (uint32_t b = 0; b < L; ++b) rev |= ((codes[s] >> (L - 1 - b)) & 1u) << b;
+        for (uint32_t hi = 0; hi < (1u << (kLutBits - L)); ++hi)
+            lut[rev | (hi << L)] = (uint32_t(s) << 23) | L;
+    }
+}
+
+int check_layer(const fluxmoe_ctx* c, uint32_t layer, bool need_encoded) {
+    if (!c) return set_error(FLUXMOE_EINVAL, "ctx is NULL");
+    if (layer >= c->d.n_layers)
+        return set_error(FLUXMOE_ERANGE, "layer %u out of range (n_layers %u)", layer, c->d.n_layers);
+    if (need_encoded && !c->layers[layer].encoded)
+        return set_error(FLUXMOE_ESTATE, "layer %u has not been encoded", layer);
+    return FLUXMOE_OK;
+}
+
+int ensure_events(fluxmoe_ctx* c) {
+    if (c->events_ready) return FLUXMOE_OK;
+    const uint32_t N = c->d.n_layers;
+    c->ev_load.assign(N, nullptr);
+    c->ev_infer.assign(N, nullptr);
+    c->ev_copied.assign(N, nullptr);
+    for (uint32_t i = 0; i < N; ++i) {
+        HIPCHECK(hipEventCreateWithFlags(&c->ev_load[i], hipEventDisableTiming));
+        HIPCHECK(hipEventCreateWithFlags(&c->ev_infer[i], hipEventDisableTiming));
+        HIPCHECK(hipEventCreateWithFlags(&c->ev_copied[i], hipEventDisableTiming));
+    }
+    for (int i = 0; i < kRing; ++i)
+        HIPCHECK(hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming));
+    for (int i = 0; i < 2; ++i)
+        HIPCHECK(hipEventCreateWithFlags(&c->ev_half_done[i], hipEventDisableTiming));
+    HIPCHECK(hipHostMalloc(reinterpret_cast<void**>(&c->pinned_cmd), size_t(kRing) * c->cmd_bytes,
+                           hipHostMallocDefault));
+    c->events_ready = true;
+    return FLUXMOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fluxmoe_last_error(void) { return g_err; }
+
+int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
+    if (!desc || !out_ctx) return set_error(FLUXMOE_EINVAL, "desc/out_ctx is NULL");
+    fluxmoe_desc d = *desc;
+    if (d.max_code_len == 0) d.max_code_len = 12;
+    if (d.n_layers == 0 || d.n_experts == 0 || d.hidden == 0 || d.ffn == 0 || d.n_slots == 0)
+        return set_error(FLUXMOE_EINVAL, "n_layers, n_experts, hidden, ffn, n_slots must be > 0");
+    if (d.hidden % 8 || d.ffn % 8)
+        return set_error(FLUXMOE_EINVAL, "hidden (%u) and ffn (%u) must be multiples of 8", d.hidden, d.ffn);
+    if (d.block_bytes != 4096)
+        return set_error(FLUXMOE_EINVAL, "block_bytes must be 4096 (got %u)", d.block_bytes);
+    if (d.max_code_len < 8 || d.max_code_len > kLutBits)
+        return set_error(FLUXMOE_EINVAL, "max_code_len must be in 8..12 (got %u)", d.max_code_len);
+    if (d.flags != 0) return set_error(FLUXMOE_EINVAL, "flags must be 0");
+    if (uint64_t(d.hidden) * d.ffn * 2 >= (1ull << 32))
+        return set_error(FLUXMOE_EINVAL, "a tensor must have fewer than 2^32 elements");
+    if (d.n_experts > 4096) return set_error(FLUXMOE_EINVAL, "n_experts must be <= 4096");
+    fluxmoe_ctx* c = new (std::nothrow) fluxmoe_ctx();
+    if (!c) return set_error(FLUXMOE_ENOMEM, "out of host memory");
+    c->d = d;
+    c->elems2 = uint64_t(d.hidden) * d.ffn;
+    c->elems13 = 2 * c->elems2;
+    c->layers.resize(d.n_layers);
+    c->pt.assign(size_t(d.n_layers) * d.n_experts, -1);
+    c->slot_owner.assign(d.n_slots, -1);
+    c->slot_last_reader.assign(d.n_slots, -1);
+    c->load_valid.assign(d.n_layers, 0);
+    c->infer_valid.assign(d.n_layers, 0);
+    c->stage.resize(d.n_layers);
+    compute_layout(c);
+    *out_ctx = c;
+    g_err[0] = 0;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_destroy(fluxmoe_ctx* c) {
+    if (!c) return FLUXMOE_OK;
+    if (c->events_ready) {
+        for (auto e : c->ev_load) if (e) (void)hipEventDestroy(e);
+        for (auto e : c->ev_infer) if (e) (void)hipEventDestroy(e);
+        for (auto e : c->ev_copied) if (e) (void)hipEventDestroy(e);
+        for (int i = 0; i < kRing; ++i) if (c->ring_ev[i]) (void)hipEventDestroy(c->ring_ev[i]);
+        for (int i = 0; i < 2; ++i) if (c->ev_half_done[i]) (void)hipEventDestroy(c->ev_half_done[i]);
+        if (c->pinned_cmd) (void)hipHostFree(c->pinned_cmd);
+    }
+    delete c;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_query_sizes(const fluxmoe_ctx* c, fluxmoe_sizes* out) {
+    if (!c || !out) return set_error(FLUXMOE_EINVAL, "ctx/out is NULL");
+    out->sigma1 = c->elems13 * 2;
+    out->sigma2 = c->elems2 * 2;
+    out->slots13_bytes = out->sigma1 * c->d.n_slots;
+    out->slots2_bytes = out->sigma2 * c->d.n_slots;
+    out->page_table_bytes = uint64_t(c->d.n_layers) * c->d.n_experts * 4;
+    // worst case: every element costs 1 raw byte + max_code_len bits, plus headers and one
+    // partly filled block per tensor
+    const uint64_t per_block = c->d.block_bytes - kHeaderBytes;
+    auto bound = [&](uint64_t elems) {
+        const uint64_t bytes = elems + (elems * c->d.max_code_len + 7) / 8;
+        return (bytes / (per_block - 8 * kGroup) + 2) * c->d.block_bytes;
+    };
+    out->layer_blob_bound = uint64_t(c->d.n_experts) * (bound(c->elems13) + bound(c->elems2));
+    out->pool_workspace_bytes = c->pool_ws_bytes;
+    return FLUXMOE_OK;
+}
+
+uint64_t fluxmoe_ffn_workspace_bytes(const fluxmoe_ctx* c, uint32_t T, uint32_t K, int shared_expert) {
+    if (!c) return 0;
+    (void)shared_expert;
+    return plan_ffn(c, T, K).bytes;
+}
+
+int fluxmoe_encode_pool(fluxmoe_ctx* c, uint32_t layer, const uint16_t* w13, const uint16_t* w2,
+                        void* dst, size_t dst_cap, size_t* dst_used, int n_threads) {
+    if (int rc = check_layer(c, layer, false)) return rc;
+    if (!w13 || !w2 || !dst || !dst_used) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    const uint32_t E = c->d.n_experts, B = c->d.block_bytes;
+    n_threads = std::max(1, std::min(n_threads, 256));
+    LayerMeta& L = c->layers[layer];
+    L.encoded = false;
+    L.bound = false;
+    const uint64_t elems[2] = {c->elems13, c->elems2};
+    const uint16_t* base[2] = {w13, w2};
+
+    auto parallel_for = [&](uint32_t count, auto&& fn) {
+        std::atomic<uint32_t> next{0};
+        auto worker = [&]() {
+            for (;;) {
+                const uint32_t i = next.fetch_add(1);
+                if (i >= count) break;
+                fn(i);
+            }
+        };
+        std::vector<std::thread> th;
+        for (int t = 1; t < n_threads; ++t) th.emplace_back(worker);
+        worker();
+        for (auto& t : th) t.join();
+    };
+
+    // 1. exponent histograms, one per tensor type over all experts
+    std::vector<std::array<uint64_t, 256>> hist(2 * size_t(E));
+    parallel_for(2 * E, [&](uint32_t i) {
+        const int ti = i / E;
+        const uint32_t e = i % E;
+        auto& h = hist[i];
+        h.fill(0);
+        const uint16_t* w = base[ti] + size_t(e) * elems[ti];
+        uint64_t local[4][256] = {};
+        uint64_t m = 0;
+        for (; m + 4 <= elems[ti]; m += 4) {
+            ++local[0][(w[m] >> 7) & 0xFF];
+            ++local[1][(w[m + 1] >> 7) & 0xFF];
+            ++local[2][(w[m + 2] >> 7) & 0xFF];
+            ++local[3][(w[m + 3] >> 7) & 0xFF];
+        }
+        for (; m < elems[ti]; ++m) ++local[0][(w[m] >> 7) & 0xFF];
+        for (int s = 0; s < 256; ++s) h[s] = local[0][s] + local[1][s] + local[2][s] + local[3][s];
+    });
+    uint16_t codes[2][256];
+    for (int ti = 0; ti < 2; ++ti) {
+        uint64_t total[256] = {};
+        for (uint32_t e = 0; e < E; ++e)
+            for (int s = 0; s < 256; ++s) total[s] += hist[size_t(ti) * E + e][s];
+        limited_code_lengths(total, c->d.max_code_len, L.lens[ti]);
+        canonical_codes(L.lens[ti], codes[ti]);
+        L.payload_bits[ti] = 0;
+        for (int s = 0; s < 256; ++s) L.payload_bits[ti] += total[s] * L.lens[ti][s];
+        L.tensors[ti].assign(E, TensorMeta());
+    }
+    // 2. block plan of every tensor
+    parallel_for(2 * E, [&](uint32_t i) {
+        const int ti = i / E;
+        const uint32_t e = i % E;
+        plan_tensor(base[ti] + size_t(e) * elems[ti], elems[ti], L.lens[ti], B,
+                    L.tensors[ti][e].first_elem);
+    });
+    // 3. blob order: down tensors (type 2) first, then fused gate/up tensors
+    uint64_t nb = 0;
+    for (int ti : {1, 0})
+        for (uint32_t e = 0; e < E; ++e) {
+            L.tensors[ti][e].first_block = nb;
+            nb += L.tensors[ti][e].n_blocks();
+        }
+    L.n_blocks = nb;
+    *dst_used = size_t(nb) * B;
+    if (size_t(nb) * B > dst_cap)
+        return set_error(FLUXMOE_ENOMEM, "layer blob needs %zu bytes, dst_cap is %zu", size_t(nb) * B, dst_cap);
+    // 4. encode
+    uint8_t* out = static_cast<uint8_t*>(dst);
+    parallel_for(2 * E, [&](uint32_t i) {
+        const int ti = i / E;
+        const uint32_t e = i % E;
+        const TensorMeta& tm = L.tensors[ti][e];
+        encode_tensor(base[ti] + size_t(e) * elems[ti], tm.first_elem, L.lens[ti], codes[ti], B,
+                      out + size_t(tm.first_block) * B);
+    });
+    L.encoded = true;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_layer_info_get(const fluxmoe_ctx* c, uint32_t layer, fluxmoe_layer_info* out) {
+    if (int rc = check_layer(c, layer, true)) return rc;
+    if (!out) return set_error(FLUXMOE_EINVAL, "out is NULL");
+    const LayerMeta& L = c->layers[layer];
+    out->n_blocks = L.n_blocks;
+    out->payload_bits[0] = L.payload_bits[0];
+    out->payload_bits[1] = L.payload_bits[1];
+    out->elements[0] = c->elems13 * c->d.n_experts;
+    out->elements[1] = c->elems2 * c->d.n_experts;
+    return FLUXMOE_OK;
+}
+
+static int type_index(int type) { return type == 1 ? 0 : (type == 2 ? 1 : -1); }
+
+int fluxmoe_code_lengths(const fluxmoe_ctx* c, uint32_t layer, int type, uint8_t out_lens[256]) {
+    if (int rc = check_layer(c, layer, true)) return rc;
+    const int ti = type_index(type);
+    if (ti < 0 || !out_lens) return set_error(FLUXMOE_EINVAL, "type must be 1 or 2, out non-NULL");
+    std::memcpy(out_lens, c->layers[layer].lens[ti], 256);
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_tensor_blocks(const fluxmoe_ctx* c, uint32_t layer, int type, uint32_t expert,
+                          uint64_t* first_block, uint64_t* n_blocks) {
+    if (int rc = check_layer(c, layer, true)) return rc;
+    const int ti = type_index(type);
+    if (ti < 0 || !first_block || !n_blocks) return set_error(FLUXMOE_EINVAL, "bad type or NULL out");
+    if (expert >= c->d.n_experts) return set_error(FLUXMOE_ERANGE, "expert %u out of range", expert);
+    const TensorMeta& tm = c->layers[layer].tensors[ti][expert];
+    *first_block = tm.first_block;
+    *n_blocks = tm.n_blocks();
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_tensor_first_elems(const fluxmoe_ctx* c, uint32_t layer, int type, uint32_t expert,
+                               uint32_t* out, size_t out_cap) {
+    if (int rc = check_layer(c, layer, true)) return rc;
+    const int ti = type_index(type);
+    if (ti < 0 || !out) return set_error(FLUXMOE_EINVAL, "bad type or NULL out");
+    if (expert >= c->d.n_experts) return set_error(FLUXMOE_ERANGE, "expert %u out of range", expert);
+    const TensorMeta& tm = c->layers[layer].tensors[ti][expert];
+    if (out_cap < tm.first_elem.size())
+        return set_error(FLUXMOE_ENOMEM, "out_cap %zu < %zu", out_cap, tm.first_elem.size());
+    std::memcpy(out, tm.first_elem.data(), tm.first_elem.size() * 4);
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_bind_arenas(fluxmoe_ctx* c, void* slots13, void* slots2, void* workspace,
+                        size_t workspace_bytes) {
+    if (!c) return set_error(FLUXMOE_EINVAL, "ctx is NULL");
+    if (!slots13 || !slots2 || !workspace) return set_error(FLUXMOE_EINVAL, "NULL arena");
+    if ((uintptr_t(slots13) | uintptr_t(slots2) | uintptr_t(workspace)) & 255)
+        return set_error(FLUXMOE_EINVAL, "arenas must be 256-byte aligned");
+    if (workspace_bytes < c->pool_ws_bytes)
+        return set_error(FLUXMOE_ENOMEM, "workspace needs at least %llu bytes",
+                         (unsigned long long)c->pool_ws_bytes);
+    int dev = 0;
+    HIPCHECK(hipGetDevice(&dev));
+    hipDeviceProp_t prop;
+    HIPCHECK(hipGetDeviceProperties(&prop, dev));
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+        return set_error(FLUXMOE_EHIP, "device is %s; this library is built for gfx950 only", prop.gcnArchName);
+    c->n_cus = prop.multiProcessorCount;
+    if (int rc = ensure_events(c)) return rc;
+    c->slots13 = static_cast<uint8_t*>(slots13);
+    c->slots2 = static_cast<uint8_t*>(slots2);
+    c->ws = static_cast<uint8_t*>(workspace);
+    c->ws_bytes = workspace_bytes;
+    HIPCHECK(hipMemset(c->ws + c->err_off, 0, 256));
+    c->arenas_bound = true;
+    for (auto& L : c->layers) L.bound = false;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_bind_layer(fluxmoe_ctx* c, uint32_t layer, const void* hbm_blocks, uint64_t n_host_blocks,
+                       const void* host_blocks, const void* check_host_copy) {
+    if (int rc = check_layer(c, layer, true)) return rc;
+    if (!c->arenas_bound) return set_error(FLUXMOE_ESTATE, "fluxmoe_bind_arenas has not been called");
+    LayerMeta& L = c->layers[layer];
+    if (n_host_blocks > L.n_blocks)
+        return set_error(FLUXMOE_ERANGE, "n_host_blocks %llu > n_blocks %llu",
+                         (unsigned long long)n_host_blocks, (unsigned long long)L.n_blocks);
+    if (n_host_blocks > 0 && !host_blocks) return set_error(FLUXMOE_EINVAL, "host_blocks is NULL");
+    if (n_host_blocks < L.n_blocks && !hbm_blocks) return set_error(FLUXMOE_EINVAL, "hbm_blocks is NULL");
+    if ((uintptr_t(hbm_blocks) | uintptr_t(host_blocks)) & 15)
+        return set_error(FLUXMOE_EINVAL, "block arenas must be 16-byte aligned");
+    if (check_host_copy) {
+        const uint8_t* blob = static_cast<const uint8_t*>(check_host_copy);
+        const uint32_t B = c->d.block_bytes;
+        for (int ti = 0; ti < 2; ++ti)
+            for (uint32_t e = 0; e < c->d.n_experts; ++e) {
+                const TensorMeta& tm = L.tensors[ti][e];
+                for (uint64_t k = 0; k < tm.n_blocks(); ++k) {
+                    uint32_t hdr[2];
+                    std::memcpy(hdr, blob + (tm.first_block + k) * B, 8);
+                    if (hdr[0] != tm.first_elem[k + 1] - tm.first_elem[k] || hdr[1] != tm.first_elem[k])
+                        return set_error(FLUXMOE_ECORRUPT,
+                                         "layer %u type %d expert %u block %llu: header (n=%u, e0=%u) "
+                                         "does not match the encoder's metadata",
+                                         layer, ti + 1, e, (unsigned long long)k, hdr[0], hdr[1]);
+                }
+            }
+    }
+    std::vector<uint32_t> lut(2 * kLutEntries);
+    build_lut(L.lens[0], lut.data());
+    build_lut(L.lens[1], lut.data() + kLutEntries);
+    HIPCHECK(hipMemcpy(c->ws + c->lut_off + uint64_t(layer) * 2 * kLutBytes, lut.data(), 2 * kLutBytes,
+                       hipMemcpyHostToDevice));
+    L.hbm = static_cast<const uint8_t*>(hbm_blocks);
+    L.host = static_cast<const uint8_t*>(host_blocks);
+    L.n_host_blocks = n_host_blocks;
+    L.bound = true;
+    c->stage[layer].valid = false;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_bind_staging(fluxmoe_ctx* c, void* staging, size_t staging_bytes) {
+    if (!c) return set_error(FLUXMOE_EINVAL, "ctx is NULL");
+    if (!staging || (uintptr_t(staging) & 255)) return set_error(FLUXMOE_EINVAL, "staging must be non-NULL, 256-byte aligned");
+    if (staging_bytes < 2ull * c->d.block_bytes) return set_error(FLUXMOE_ENOMEM, "staging too small");
+    c->staging = static_cast<uint8_t*>(staging);
+    c->staging_bytes = staging_bytes;
+    for (auto& s : c->stage) s.valid = false;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_reset_page_table(fluxmoe_ctx* c, int32_t* page_table, void* stream) {
+    if (!c || !page_table) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    HIPCHECK(launch_fill_i32(page_table, -1, uint64_t(c->d.n_layers) * c->d.n_experts,
+                             static_cast<hipStream_t>(stream)));
+    std::fill(c->pt.begin(), c->pt.end(), -1);
+    std::fill(c->slot_owner.begin(), c->slot_owner.end(), -1);
+    return FLUXMOE_OK;
+}
+
+static int validate_ids(const fluxmoe_ctx* c, const int32_t* ids, uint32_t n) {
+    if (n > c->d.n_experts) return set_error(FLUXMOE_EINVAL, "n %u > n_experts %u", n, c->d.n_experts);
+    if (n && !ids) return set_error(FLUXMOE_EINVAL, "expert_ids is NULL");
+    std::vector<uint8_t> seen(c->d.n_experts, 0);
+    for (uint32_t i = 0; i < n; ++i) {
+        if (ids[i] < 0 || uint32_t(ids[i]) >= c->d.n_experts)
+            return set_error(FLUXMOE_ERANGE, "expert id %d out of range [0, %u)", ids[i], c->d.n_experts);
+        if (seen[ids[i]]++) return set_error(FLUXMOE_EINVAL, "expert id %d listed twice", ids[i]);
+    }
+    return FLUXMOE_OK;
+}
+
+// Copies of the listed experts' host-tier blocks into the layer's staging half.
+static int stage_host_blocks(fluxmoe_ctx* c, uint32_t layer, const int32_t* ids, uint32_t n,
+                             hipStream_t s) {
+    LayerMeta& L = c->layers[layer];
+    StageState& st = c->stage[layer];
+    st.valid = false;
+    st.off[0].assign(c->d.n_experts, -1);
+    st.off[1].assign(c->d.n_experts, -1);
+    if (L.n_host_blocks == 0) { st.valid = true; return FLUXMOE_OK; }
+    if (!c->staging) return set_error(FLUXMOE_ESTATE, "layer %u has host-tier blocks but no staging buffer is bound", layer);
+    const uint32_t B = c->d.block_bytes;
+    const int half = layer & 1;
+    const uint64_t half_bytes = (c->staging_bytes / 2) / B * B;
+    uint8_t* base = c->staging + half * half_bytes;
+    std::vector<int32_t> sorted(ids, ids + n);
+    std::sort(sorted.begin(), sorted.end());
+    struct Range { uint64_t a, b, dst; };
+    std::vector<Range> ranges;
+    uint64_t cursor = 0;
+    for (int ti : {1, 0})
+        for (int32_t e : sorted) {
+            const TensorMeta& tm = L.tensors[ti][e];
+            const uint64_t a = tm.first_block, b = std::min<uint64_t>(tm.first_block + tm.n_blocks(), L.n_host_blocks);
+            if (a >= b) continue;
+            st.off[ti][e] = int64_t(cursor);
+            if (!ranges.empty() && ranges.back().b == a) ranges.back().b = b;
+            else ranges.push_back({a, b, cursor});
+            cursor += (b - a) * B;
+        }
+    if (cursor > half_bytes)
+        return set_error(FLUXMOE_ENOMEM, "staging half holds %llu bytes, layer %u needs %llu",
+                         (unsigned long long)half_bytes, layer, (unsigned long long)cursor);
+    if (c->half_done_valid[half]) HIPCHECK(hipStreamWaitEvent(s, c->ev_half_done[half], 0));
+    for (const Range& r : ranges)
+        HIPCHECK(hipMemcpyAsync(base + r.dst, L.host + r.a * B, (r.b - r.a) * B, hipMemcpyHostToDevice, s));
+    HIPCHECK(hipEventRecord(c->ev_copied[layer], s));
+    st.valid = true;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_prefetch_host(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, uint32_t n,
+                          void* copy_stream) {
+    if (int rc = check_layer(c, layer, true)) return rc;
+    if (!c->layers[layer].bound) return set_error(FLUXMOE_ESTATE, "layer %u is not bound", layer);
+    if (int rc = validate_ids(c, expert_ids, n)) return rc;
+    return stage_host_blocks(c, layer, expert_ids, n, static_cast<hipStream_t>(copy_stream));
+}
+
+int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, uint32_t n,
+                        int32_t* page_table, const int32_t* dst_slots, void* stream_v) {
+    if (int rc = check_layer(c, layer, true)) return rc;
+    LayerMeta& L = c->layers[layer];
+    if (!c->arenas_bound || !L.bound) return set_error(FLUXMOE_ESTATE, "arenas or layer %u not bound", layer);
+    if (!page_table) return set_error(FLUXMOE_EINVAL, "page_table is NULL");
+    if (int rc = validate_ids(c, expert_ids, n)) return rc;
+    if (n && !dst_slots) return set_error(FLUXMOE_EINVAL, "dst_slots is NULL");
+    {
+        std::vector<uint8_t> seen(c->d.n_slots, 0);
+        for (uint32_t i = 0; i < n; ++i) {
+            if (dst_slots[i] < 0 || uint32_t(dst_slots[i]) >= c->d.n_slots)
+                return set_error(FLUXMOE_ERANGE, "slot %d out of range [0, %u)", dst_slots[i], c->d.n_slots);
+            if (seen[dst_slots[i]]++) return set_error(FLUXMOE_EINVAL, "slot %d listed twice", dst_slots[i]);
+        }
+    }
+    if (n == 0) return FLUXMOE_OK;
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const uint32_t E = c->d.n_experts, B = c->d.block_bytes;
+
+    // host-tier parts must be staged for exactly these experts
+    bool need_host = false;
+    for (uint32_t i = 0; i < n && !need_host; ++i)
+        for (int ti = 0; ti < 2; ++ti)
+            if (L.tensors[ti][expert_ids[i]].first_block < L.n_host_blocks) need_host = true;
+    bool wait_copy = false;
+    if (need_host) {
+        StageState& st = c->stage[layer];
+        bool staged = st.valid;
+        for (uint32_t i = 0; i < n && staged; ++i)
+            for (int ti = 0; ti < 2; ++ti)
+                if (L.tensors[ti][expert_ids[i]].first_block < L.n_host_blocks && st.off[ti][expert_ids[i]] < 0)
+                    staged = false;
+        if (!staged) {
+            if (int rc = stage_host_blocks(c, layer, expert_ids, n, stream)) return rc;
+        } else {
+            wait_copy = true;
+        }
+    }
+
+    // ring slot for the command buffer
+    const int slot = c->ring_next;
+    if (c->ring_used[slot]) HIPCHECK(hipEventSynchronize(c->ring_ev[slot]));
+    uint8_t* hcmd = c->pinned_cmd + size_t(slot) * c->cmd_bytes;
+    uint8_t* dcmd = c->ws + c->cmd_off + size_t(slot) * c->cmd_bytes;
+    DecodeCmd* cmd = reinterpret_cast<DecodeCmd*>(hcmd);
+    const uint32_t jobs_off[2] = {uint32_t(sizeof(DecodeCmd)),
+                                  uint32_t(sizeof(DecodeCmd) + c->max_jobs * sizeof(DecodeJob))};
+    const uint32_t upd_off = uint32_t(sizeof(DecodeCmd) + 2ull * c->max_jobs * sizeof(DecodeJob));
+    std::memset(cmd, 0, sizeof(DecodeCmd));
+
+    const int half = layer & 1;
+    const uint64_t half_bytes = c->staging ? (c->staging_bytes / 2) / B * B : 0;
+    for (int ti = 0; ti < 2; ++ti) {
+        DecodeJob* jobs = reinterpret_cast<DecodeJob*>(hcmd + jobs_off[ti]);
+        uint32_t nj = 0, blocks = 0;
+        const uint64_t sigma = (ti == 0 ? c->elems13 : c->elems2) * 2;
+        uint8_t* arena = ti == 0 ? c->slots13 : c->slots2;
+        for (uint32_t i = 0; i < n; ++i) {
+            const TensorMeta& tm = L.tensors[ti][expert_ids[i]];
+            const uint64_t a = tm.first_block, b = tm.first_block + tm.n_blocks();
+            const uint64_t hb = std::min(b, std::max(a, L.n_host_blocks));   // host part is [a, hb)
+            const uint64_t dst = uint64_t(uintptr_t(arena)) + uint64_t(dst_slots[i]) * sigma;
+            if (hb > a) {
+                const uint8_t* src = c->staging + half * half_bytes + c->stage[layer].off[ti][expert_ids[i]];
+                jobs[nj++] = DecodeJob{uint64_t(uintptr_t(src)), dst, blocks, uint32_t(hb - a),
+                                       uint32_t(ti == 0 ? c->elems13 : c->elems2), 0};
+                blocks += uint32_t(hb - a);
+            }
+            if (b > hb) {
+                const uint8_t* src = L.hbm + (hb - L.n_host_blocks) * B;
+                jobs[nj++] = DecodeJob{uint64_t(uintptr_t(src)), dst, blocks, uint32_t(b - hb),
+                                       uint32_t(ti == 0 ? c->elems13 : c->elems2), 0};
+                blocks += uint32_t(b - hb);
+            }
+        }
+        cmd->n_jobs[ti] = nj;
+        cmd->total_blocks[ti] = blocks;
+    }
+
+    // page-table transitions on the host mirror; the touched entries go to the device
+    std::vector<int64_t> touched;
+    std::vector<int32_t> wait_layers;
+    for (uint32_t i = 0; i < n; ++i) {
+        const int64_t key = int64_t(layer) * E + expert_ids[i];
+        const int32_t s = dst_slots[i];
+        const int32_t old_slot = c->pt[key];
+        if (old_slot >= 0 && old_slot != s) c->slot_owner[old_slot] = -1;
+        const int64_t prev = c->slot_owner[s];
+        if (prev >= 0 && prev != key) {
+            c->pt[prev] = -1;
+            touched.push_back(prev);
+        }
+        c->pt[key] = s;
+        c->slot_owner[s] = key;
+        touched.push_back(key);
+        const int32_t lr = c->slot_last_reader[s];
+        if (lr >= 0 && c->infer_valid[lr] &&
+            std::find(wait_layers.begin(), wait_layers.end(), lr) == wait_layers.end())
+            wait_layers.push_back(lr);
+        c->slot_last_reader[s] = -1;
+    }
+    std::sort(touched.begin(), touched.end());
+    touched.erase(std::unique(touched.begin(), touched.end()), touched.end());
+    int32_t* upd = reinterpret_cast<int32_t*>(hcmd + upd_off);
+    for (size_t i = 0; i < touched.size(); ++i) {
+        upd[2 * i] = int32_t(touched[i]);
+        upd[2 * i + 1] = c->pt[touched[i]];
+    }
+    cmd->n_pt_updates = uint32_t(touched.size());
+
+    // enqueue: WAR waits, host-tier copies, command upload, decode, events
+    for (int32_t lr : wait_layers) HIPCHECK(hipStreamWaitEvent(stream, c->ev_infer[lr], 0));
+    if (wait_copy) HIPCHECK(hipStreamWaitEvent(stream, c->ev_copied[layer], 0));
+    const size_t used = upd_off + touched.size() * 8;
+    HIPCHECK(hipMemcpyAsync(dcmd, hcmd, used, hipMemcpyHostToDevice, stream));
+
+    DecodeArgs args{};
+    args.cmd = reinterpret_cast<const DecodeCmd*>(dcmd);
+    args.jobs_offset[0] = jobs_off[0];
+    args.jobs_offset[1] = jobs_off[1];
+    args.upd_offset = upd_off;
+    args.lut[0] = reinterpret_cast<const uint32_t*>(c->ws + c->lut_off + (uint64_t(layer) * 2 + 0) * kLutBytes);
+    args.lut[1] = reinterpret_cast<const uint32_t*>(c->ws + c->lut_off + (uint64_t(layer) * 2 + 1) * kLutBytes);
+    args.page_table = page_table;
+    args.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
+    const int waves_per_wg = 8;
+    const uint64_t total = uint64_t(cmd->total_blocks[0]) + cmd->total_blocks[1];
+    uint32_t n_wg = uint32_t(std::min<uint64_t>(uint64_t(c->n_cus) * 3, (total + waves_per_wg - 1) / waves_per_wg));
+    n_wg = std::max(n_wg, 2u);
+    uint32_t split = uint32_t((uint64_t(n_wg) * cmd->total_blocks[1] + total / 2) / total);
+    split = std::min(std::max(split, 1u), n_wg - 1);
+    args.wg_split = split;
+    HIPCHECK(launch_decode(args, n_wg, waves_per_wg, stream));
+    HIPCHECK(hipEventRecord(c->ring_ev[slot], stream));
+    c->ring_used[slot] = true;
+    c->ring_next = (slot + 1) % kRing;
+    if (need_host) {
+        HIPCHECK(hipEventRecord(c->ev_half_done[half], stream));
+        c->half_done_valid[half] = true;
+        c->stage[layer].valid = false;
+    }
+    HIPCHECK(hipEventRecord(c->ev_load[layer], stream));
+    c->load_valid[layer] = 1;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_release(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, uint32_t n,
+                    int32_t* page_table, void* stream_v) {
+    if (int rc = check_layer(c, layer, false)) return rc;
+    if (!c->arenas_bound) return set_error(FLUXMOE_ESTATE, "fluxmoe_bind_arenas has not been called");
+    if (!page_table) return set_error(FLUXMOE_EINVAL, "page_table is NULL");
+    if (expert_ids) {
+        if (int rc = validate_ids(c, expert_ids, n)) return rc;
+    } else if (n != 0) {
+        return set_error(FLUXMOE_EINVAL, "expert_ids is NULL but n is %u", n);
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    const uint32_t E = c->d.n_experts;
+    const int slot = c->ring_next;
+    if (c->ring_used[slot]) HIPCHECK(hipEventSynchronize(c->ring_ev[slot]));
+    uint8_t* hcmd = c->pinned_cmd + size_t(slot) * c->cmd_bytes;
+    uint8_t* dcmd = c->ws + c->cmd_off + size_t(slot) * c->cmd_bytes;
+    int32_t* upd = reinterpret_cast<int32_t*>(hcmd);
+    uint32_t m = 0;
+    const uint32_t count = expert_ids ? n : E;
+    for (uint32_t i = 0; i < count; ++i) {
+        const int64_t key = int64_t(layer) * E + (expert_ids ? expert_ids[i] : int32_t(i));
+        const int32_t s = c->pt[key];
+        if (s < 0) continue;
+        c->pt[key] = -1;
+        c->slot_owner[s] = -1;       // the slot keeps its last-reader layer: reuse still waits
+        upd[2 * m] = int32_t(key);
+        upd[2 * m + 1] = -1;
+        ++m;
+    }
+    if (m == 0) return FLUXMOE_OK;
+    HIPCHECK(hipMemcpyAsync(dcmd, hcmd, size_t(m) * 8, hipMemcpyHostToDevice, stream));
+    HIPCHECK(launch_apply_updates(page_table, dcmd, m, stream));
+    HIPCHECK(hipEventRecord(c->ring_ev[slot], stream));
+    c->ring_used[slot] = true;
+    c->ring_next = (slot + 1) % kRing;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, uint32_t T,
+                       const int32_t* topk_ids, const float* topk_w, uint32_t K,
+                       const int32_t* page_table, float* out, uint32_t flags, void* stream_v) {
+    if (int rc = check_layer(c, layer, false)) return rc;
+    if (!c->arenas_bound) return set_error(FLUXMOE_ESTATE, "fluxmoe_bind_arenas has not been called");
+    if (T == 0) return FLUXMOE_OK;
+    if (!tokens || !topk_ids || !topk_w || !page_table || !out) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    if (K == 0 || K > c->d.n_experts) return set_error(FLUXMOE_EINVAL, "K must be in 1..n_experts");
+    if (flags & ~3u) return set_error(FLUXMOE_EINVAL, "unknown flags 0x%x", flags);
+    if (uint64_t(T) * K >= (1ull << 31) || T > 65535) return set_error(FLUXMOE_EINVAL, "T too large");
+    if ((uintptr_t(tokens) | uintptr_t(out)) & 15) return set_error(FLUXMOE_EINVAL, "tokens/out must be 16-byte aligned");
+    const FfnPlan p = plan_ffn(c, T, K);
+    if (c->pool_ws_bytes + p.bytes > c->ws_bytes)
+        return set_error(FLUXMOE_ENOMEM, "workspace has %zu bytes, T=%u K=%u needs %llu", c->ws_bytes, T, K,
+                         (unsigned long long)(c->pool_ws_bytes + p.bytes));
+    if (p.tiles_cap > 65535) return set_error(FLUXMOE_EINVAL, "too many row tiles (%u)", p.tiles_cap);
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    uint8_t* w = c->ws + c->pool_ws_bytes;
+    FfnArgs a{};
+    a.tokens = tokens;
+    a.topk_ids = topk_ids;
+    a.topk_w = topk_w;
+    a.page_table = page_table + size_t(layer) * c->d.n_experts;
+    a.slots13 = reinterpret_cast<const uint16_t*>(c->slots13);
+    a.slots2 = reinterpret_cast<const uint16_t*>(c->slots2);
+    a.out = out;
+    a.T = T; a.K = K; a.H = c->d.hidden; a.F = c->d.ffn; a.E = c->d.n_experts;
+    a.flags = flags;
+    a.expert_count = reinterpret_cast<int32_t*>(w + p.off_count);
+    a.expert_offset = reinterpret_cast<int32_t*>(w + p.off_offset);
+    a.sorted_pair = reinterpret_cast<int32_t*>(w + p.off_sorted);
+    a.pair_pos = reinterpret_cast<int32_t*>(w + p.off_pos);
+    a.tile_expert = reinterpret_cast<int32_t*>(w + p.off_tile_e);
+    a.tile_row0 = reinterpret_cast<int32_t*>(w + p.off_tile_r);
+    a.n_tiles = reinterpret_cast<int32_t*>(w + p.off_ntiles);
+    a.hbuf = reinterpret_cast<uint16_t*>(w + p.off_h);
+    a.ybuf = reinterpret_cast<float*>(w + p.off_y);
+    a.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
+    a.pairs_cap = p.pairs_cap; a.tiles_cap = p.tiles_cap; a.m_tile = p.m_tile; a.ksplit = p.ksplit;
+
+    if (c->load_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_load[layer], 0));
+    HIPCHECK(launch_ffn(a, c->n_cus, stream));
+    HIPCHECK(hipEventRecord(c->ev_infer[layer], stream));
+    c->infer_valid[layer] = 1;
+    const int64_t lo = int64_t(layer) * c->d.n_experts, hi = lo + c->d.n_experts;
+    for (uint32_t s = 0; s < c->d.n_slots; ++s)
+        if (c->slot_owner[s] >= lo && c->slot_owner[s] < hi) c->slot_last_reader[s] = int32_t(layer);
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_device_errors(fluxmoe_ctx* c, uint32_t* out_flags) {
+    if (!c || !out_flags) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    if (!c->arenas_bound) return set_error(FLUXMOE_ESTATE, "fluxmoe_bind_arenas has not been called");
+    HIPCHECK(hipDeviceSynchronize());
+    HIPCHECK(hipMemcpy(out_flags, c->ws + c->err_off, 4, hipMemcpyDeviceToHost));
+    HIPCHECK(hipMemset(c->ws + c->err_off, 0, 4));
+    return FLUXMOE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Device-side structures and kernel launchers of libfluxmoe.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace fluxmoe {
+
+constexpr uint32_t kHeaderBytes = 136;   // n, e0, sub_bits[64]
+constexpr uint32_t kSubStreams = 64;
+constexpr uint32_t kGroup = 64;          // block element counts are multiples of this
+constexpr uint32_t kLutBits = 12;        // decode tables index 12 stream bits
+constexpr uint32_t kLutEntries = 1u << kLutBits;
+
+#if defined(__HIPCC__)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+// Streaming (non-temporal) 16-byte accesses: data that is touched once.
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_stream16(void* p, const uint4& v) {
+    const u32x4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+}
+#endif
+
+// One contiguous run of blocks of one tensor, decoded into one slot.
+struct DecodeJob {
+    uint64_t src;           // address of the run's first block (device memory)
+    uint64_t dst;           // address of the tensor's first element in its slot
+    uint32_t first_block;   // index of the run's first block in this type's block list
+    uint32_t n_blocks;
+    uint32_t tensor_elems;  // elements of the whole tensor (bounds every write)
+    uint32_t pad;
+};
+static_assert(sizeof(DecodeJob) == 32, "DecodeJob layout");
+
+// Header of a command buffer; the job lists and page-table updates follow it.
+struct DecodeCmd {
+    uint32_t n_jobs[2];        // [0] type 1 (gate/up), [1] type 2 (down)
+    uint32_t total_blocks[2];
+    uint32_t n_pt_updates;
+    uint32_t pad[3];
+};
+static_assert(sizeof(DecodeCmd) == 32, "DecodeCmd layout");
+
+struct DecodeArgs {
+    const DecodeCmd* cmd;        // device
+    uint32_t jobs_offset[2];     // byte offsets of the two job lists from cmd
+    uint32_t upd_offset;         // byte offset of the int2 (index, value) page-table updates
+    uint32_t wg_split;           // workgroups [0, wg_split) decode type 2, the rest type 1
+    const uint32_t* lut[2];      // device decode tables, [0] type 1, [1] type 2
+    int32_t* page_table;         // device
+    uint32_t* error_word;        // device
+};
+
+hipError_t launch_decode(const DecodeArgs& args, uint32_t n_workgroups, int waves_per_wg,
+                         hipStream_t stream);
+hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t stream);
+// page_table[upd[i].x] = upd[i].y for i < n (upd: device int2 list)
+hipError_t launch_apply_updates(int32_t* page_table, const void* upd, uint32_t n, hipStream_t stream);
+
+// ---------------------------------------------------------------- expert FFN
+struct FfnArgs {
+    const uint16_t* tokens;      // BF16 [T][H]
+    const int32_t* topk_ids;     // [T][K]
+    const float* topk_w;         // [T][K]
+    const int32_t* page_table;   // this layer's row: [n_experts]
+    const uint16_t* slots13;     // type-1 arena
+    const uint16_t* slots2;      // type-2 arena
+    float* out;                  // [T][H]
+    uint32_t T, K, H, F, E;
+    uint32_t flags;
+    // workspace carve-up (device)
+    int32_t* expert_count;       // [E + 1]
+    int32_t* expert_offset;      // [E + 2]
+    int32_t* sorted_pair;        // [pairs_cap]  pair index (t * K + k), grouped by expert
+    int32_t* pair_pos;           // [pairs_cap]  position of a pair in sorted order, -1 = skipped
+    int32_t* tile_expert;        // [tiles_cap]
+    int32_t* tile_row0;          // [tiles_cap]  first sorted row of the tile
+    int32_t* n_tiles;            // [1]
+    uint16_t* hbuf;              // BF16 [pairs_cap][F]
+    float* ybuf;                 // FP32 [ksplit][pairs_cap][H]
+    uint32_t* error_word;
+    uint32_t pairs_cap, tiles_cap, m_tile, ksplit;
+};
+
+hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream);
+
+}  // namespace fluxmoe

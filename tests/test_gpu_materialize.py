@@ -1,0 +1,182 @@
+"""GPU parity: decoded weights and page placement must equal the oracle bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import codec, paging
+from paper_2604_02715_amd import binding as B
+from paper_2604_02715_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def run_against_model(cfg, calls, seed=0, weights=None):
+    """calls: list of (layer, expert_ids, dst_slots).  Compares every slot byte and the whole
+    page table with the CPU placement model after every call."""
+    from gpu_common import build_pool, u16
+    pool, dense = build_pool(cfg, seed=seed, weights=weights)
+    try:
+        pool.poison_slots(0x7FC1)
+        pool.reset_page_table()
+        model = paging.PagedSlots(cfg.n_layers, cfg.n_experts, cfg.n_slots, cfg.hidden, cfg.ffn)
+        for layer, ids, slots in calls:
+            print("materialize", cfg.name, "layer", layer, "ids", ids, "slots", slots, flush=True)
+            w13, w2 = dense[layer]
+            if slots == "release":
+                model.release(layer, ids)
+                pool.release(layer, ids)
+                torch.cuda.synchronize()
+                assert np.array_equal(pool.page_table.cpu().numpy(), model.page_table)
+                continue
+            model.materialize(layer, ids, slots, lambda e: inputs.bits_u16(w13[e]).reshape(-1),
+                              lambda e: inputs.bits_u16(w2[e]).reshape(-1))
+            pool.materialize(layer, ids, slots)
+            torch.cuda.synchronize()
+            assert pool.device_errors() == 0
+            assert np.array_equal(u16(pool.slots13).reshape(cfg.n_slots, -1), model.slots13)
+            assert np.array_equal(u16(pool.slots2).reshape(cfg.n_slots, -1), model.slots2)
+            assert np.array_equal(pool.page_table.cpu().numpy(), model.page_table)
+    finally:
+        pool.close()
+
+
+def test_c1_tiny_all_experts_shuffled_slots():
+    cfg = inputs.CONFIGS["c1_tiny"]
+    perm = inputs.slot_permutation(cfg.n_slots, cfg.name, 0)
+    run_against_model(cfg, [(0, list(range(cfg.n_experts)), list(perm))])
+
+
+def test_subsets_eviction_moves_and_untouched_slots():
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=6, hidden=128, ffn=192, n_slots=5,
+                        n_layers=2)
+    calls = [
+        (0, [4, 1], [2, 0]),          # slots 1, 3, 4 stay poisoned
+        (1, [5], [2]),                # layer 1 evicts layer 0's expert 4
+        (0, [1], [3]),                # move: slot 0 becomes free
+        (0, [1, 2], [1, 3]),          # swap-like remap inside one call
+        (0, [], []),                  # empty call
+        (0, [2, 5], "release"),       # expert 5 is not mapped: no effect for it
+        (0, [2], [0]),                # back into a different slot
+        (1, None, "release"),         # whole layer
+        (1, [0, 1, 2, 3, 4], [4, 3, 2, 1, 0]),
+        (0, [3], [4]),
+    ]
+    run_against_model(cfg, calls)
+
+
+def test_ragged_shapes_single_group_tail():
+    # 8 x 8 = 64 elements for the down tensor: one block holding one group of 64
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=3, hidden=8, ffn=8, n_slots=3)
+    run_against_model(cfg, [(0, [2, 0, 1], [0, 1, 2])])
+    # sizes that leave a short last block and partial last iterations
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=2, hidden=72, ffn=200, n_slots=4)
+    run_against_model(cfg, [(0, [1, 0], [3, 1])])
+
+
+def test_adversarial_bit_patterns():
+    """NaN/Inf/zero/subnormal words, a single exponent, all 256 exponents, codes at the length
+    limit: the decoder must still return the exact bits."""
+    adv = inputs.adversarial_tensors()
+    H, F = 64, 128                                           # 8192-element down tensors
+    names = sorted(adv)
+    E = len(names)
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=E, hidden=H, ffn=F, n_slots=E)
+    w2 = np.stack([np.resize(adv[n], H * F) for n in names]).reshape(E, F, H)
+    w13 = np.stack([np.resize(adv[n][::-1], 2 * H * F) for n in names]).reshape(E, 2, H, F)
+    weights = {0: (torch.from_numpy(w13.view(np.int16)).view(torch.bfloat16),
+                   torch.from_numpy(w2.view(np.int16)).view(torch.bfloat16))}
+    run_against_model(cfg, [(0, list(range(E)), list(range(E))[::-1])], weights=weights)
+
+
+def test_gpu_decodes_streams_written_by_the_oracle_encoder():
+    """The pool bytes come from oracle/codec.py, not from the library's encoder."""
+    from gpu_common import build_pool, assert_slot_equals
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=4, hidden=128, ffn=256, n_slots=4)
+    pool, dense = build_pool(cfg)
+    try:
+        w13, w2 = dense[0]
+        opool = codec.encode_layer(inputs.bits_u16(w13), inputs.bits_u16(w2))
+        # same block layout as the library (both follow the same container rules)
+        for d in (1, 2):
+            for e in range(cfg.n_experts):
+                assert B.fluxmoe_tensor_blocks(pool.ctx, 0, d, e) == (
+                    opool["tensor_blocks"][(d, e)][0],
+                    opool["tensor_blocks"][(d, e)][1] - opool["tensor_blocks"][(d, e)][0])
+        blob = torch.from_numpy(opool["blocks"].reshape(-1).copy())
+        pool.bind_layer(0, blob)
+        pool.poison_slots()
+        pool.reset_page_table()
+        pool.materialize(0, [0, 1, 2, 3], [3, 2, 1, 0])
+        torch.cuda.synchronize()
+        assert pool.device_errors() == 0
+        for e in range(4):
+            assert_slot_equals(pool, 3 - e, w13[e], w2[e])
+    finally:
+        pool.close()
+
+
+def test_oracle_decodes_the_library_pool_and_matches_the_gpu():
+    from gpu_common import build_pool, u16
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=2, hidden=128, ffn=256, n_slots=2)
+    pool, dense = build_pool(cfg)
+    try:
+        w13, w2 = dense[0]
+        blob_t = pool.encode_layer(0, w13, w2)       # re-encoding unbinds the layer
+        pool.bind_layer(0, blob_t)
+        blob = blob_t.numpy().reshape(-1, 4096)
+        pool.reset_page_table()
+        pool.materialize(0, [0, 1], [1, 0])
+        torch.cuda.synchronize()
+        for e in range(2):
+            b0, nb = B.fluxmoe_tensor_blocks(pool.ctx, 0, 1, e)
+            lens = B.fluxmoe_code_lengths(pool.ctx, 0, 1)
+            want = codec.decode_tensor(blob[b0:b0 + nb], lens, 2 * cfg.hidden * cfg.ffn)
+            assert np.array_equal(u16(pool.slot13(1 - e)), want)
+    finally:
+        pool.close()
+
+
+def test_corrupt_block_is_skipped_and_flagged_never_written_out_of_bounds():
+    from gpu_common import build_pool, u16
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=2, hidden=128, ffn=256, n_slots=2)
+    pool, dense = build_pool(cfg)
+    try:
+        w13, w2 = dense[0]
+        blob = pool.encode_layer(0, w13, w2).clone()
+        b0, nb = B.fluxmoe_tensor_blocks(pool.ctx, 0, 2, 1)
+        view = blob.numpy().reshape(-1, 4096)
+        first = B.fluxmoe_tensor_first_elems(pool.ctx, 0, 2, 1)
+        view[b0 + 1, 4:8] = np.frombuffer(np.uint32(cfg.hidden * cfg.ffn).tobytes(), dtype=np.uint8)
+        with pytest.raises(B.FluxmoeError) as ei:
+            pool.bind_layer(0, blob, check=True)          # host check sees it
+        assert ei.value.status == -3
+        pool.bind_layer(0, blob, check=False)             # bound unchecked: the kernel must cope
+        pool.poison_slots(0x7FC1)
+        pool.reset_page_table()
+        pool.materialize(0, [0, 1], [0, 1])
+        torch.cuda.synchronize()
+        assert pool.device_errors() == 1
+        got = u16(pool.slot2(1))
+        want = inputs.bits_u16(w2[1]).reshape(-1).copy()
+        want[first[1]:first[2]] = 0x7FC1                  # the bad block's range stays poisoned
+        assert np.array_equal(got, want)
+        assert np.array_equal(u16(pool.slot2(0)), inputs.bits_u16(w2[0]).reshape(-1))
+    finally:
+        pool.close()
+
+
+def test_argument_errors_enqueue_nothing():
+    from gpu_common import build_pool
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=3, hidden=64, ffn=64, n_slots=2)
+    pool, _ = build_pool(cfg)
+    try:
+        pool.reset_page_table()
+        for ids, slots, status in (([0, 0], [0, 1], -1), ([0, 1], [1, 1], -1), ([3], [0], -4),
+                                   ([0], [2], -4), ([-1], [0], -4)):
+            with pytest.raises(B.FluxmoeError) as ei:
+                pool.materialize(0, ids, slots)
+            assert ei.value.status == status
+        torch.cuda.synchronize()
+        assert (pool.page_table.cpu().numpy() == -1).all()
+    finally:
+        pool.close()

@@ -146,3 +146,9 @@ def test_placement_model():
     assert ps.page_table[0, 1] == 1 and ps.page_table[0, 2] == 3
     assert (ps.slots13[1] == 101).all() and (ps.slots13[3] == 102).all()
     assert paging.waves([5, 1, 9, 3, 7], 2) == [[1, 3], [5, 7], [9]]
+    # release: mappings go, bytes stay, unmapped ids are ignored
+    ps.release(0, [1, 5])
+    assert ps.page_table[0, 1] == -1 and ps.owner[1] is None and (ps.slots13[1] == 101).all()
+    assert ps.page_table[0, 2] == 3
+    ps.release(0)
+    assert (ps.page_table[0] == -1).all() and ps.page_table[1, 5] == 2
