@@ -1,0 +1,192 @@
+#!/usr/bin/env python3
+"""Benchmark of the expert-materialization hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input: materialize the
+routed experts of a layer from the compressed HBM pool into their staging slots (decode +
+paged scatter + page-table update), then run the routed SwiGLU expert FFN on them.  The
+default workload is the Mixtral-8x7B-shaped layer (8 experts, H 4096, F 14336, 256 decode
+tokens, top-2; all 8 experts materialized every step).  Prints ONE JSON line.
+
+  value      dense BF16 bytes materialized per second of whole-step time (GB/s, GB = 1e9 B),
+             the paper's throughput definition (Sec. 6.3, Exp#3) applied to the whole step
+  roofline   the decode kernel against HBM peak: algorithmic bytes (compressed blocks read +
+             dense bytes written) per launch / mean launch duration from HIP events recorded
+             around the kernel on its own stream
+  cpu_baseline  the CPU oracle's decoder timed here on a bounded sample of the same pool
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="c2_mixtral", help="c1_tiny | c2_mixtral | c3_qwen3next | c4_glm45")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); "
+                 "run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2604_02715_amd import binding as B
+    from paper_2604_02715_amd import harness, inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cfg = inputs.CONFIGS[args.config]
+    t_setup = time.time()
+    pool = harness.ExpertPool(cfg)
+    w13, w2 = harness.make_layer_on_host(cfg, 0, 0, gen_device="cuda")
+    blob = pool.encode_layer(0, w13, w2)
+    pool.bind_layer(0, blob)
+    info = B.fluxmoe_layer_info_get(pool.ctx, 0)
+    x = inputs.activations(cfg).cuda()
+    ids_np, g_np = inputs.routing(cfg)
+    ids, g = torch.from_numpy(ids_np).cuda(), torch.from_numpy(g_np).cuda()
+    out = torch.zeros((cfg.tokens, cfg.hidden), dtype=torch.float32, device="cuda")
+    union = inputs.routed_union(ids_np)
+    n_fit = min(len(union), cfg.n_slots)
+    wave = union[:n_fit]                       # one wave per step (configs whose union fits)
+    slots = inputs.slot_permutation(cfg.n_slots, cfg.name, "bench")[:n_fit]
+    flags = B.FFN_SKIP_UNMAPPED if n_fit < len(union) else 0
+    pool.reset_page_table()
+    setup_s = time.time() - t_setup
+
+    def step():
+        pool.materialize(0, wave, slots)
+        pool.expert_ffn(0, x, ids, g, out, flags)
+
+    # bytes one step moves / computes
+    dense_bytes = int(n_fit) * (cfg.sigma1 + cfg.sigma2)
+    comp_blocks = 0
+    for e in wave:
+        for d in (1, 2):
+            comp_blocks += B.fluxmoe_tensor_blocks(pool.ctx, 0, d, int(e))[1]
+    comp_bytes = comp_blocks * 4096
+    pairs = int(np.isin(ids_np, wave).sum())
+    flops = 6.0 * cfg.hidden * cfg.ffn * pairs
+
+    if not args.no_check:
+        step()
+        torch.cuda.synchronize()
+        assert pool.device_errors() == 0
+        for e, s in zip(wave, slots):
+            ref = w13[int(e)].reshape(-1).view(torch.int16).cuda()
+            assert torch.equal(pool.slot13(int(s)), ref), "decode mismatch"
+            ref = w2[int(e)].reshape(-1).view(torch.int16).cuda()
+            assert torch.equal(pool.slot2(int(s)), ref), "decode mismatch"
+        del ref
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.fluxmoe_profile_enable(pool.ctx, True)
+    B.fluxmoe_profile_collect(pool.ctx)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = B.fluxmoe_profile_collect(pool.ctx)
+    B.fluxmoe_profile_enable(pool.ctx, False)
+    assert pool.device_errors() == 0
+
+    ms_per_step = elapsed / args.steps * 1e3
+    decode_ms = prof["decode"][0] / max(1, prof["decode"][1])
+    ffn_ms = sum(prof[k][0] for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")) / args.steps
+    achieved = (comp_bytes + dense_bytes) / (decode_ms * 1e-3) / 1e9
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "decode_traffic.json")
+    if os.path.exists(tpath):
+        rec = json.load(open(tpath))
+        if rec.get("workload") == cfg.name:
+            traffic = rec.get("hbm_bytes_per_launch")
+
+    result = {
+        "metric": "expert_materialization_dense_out",
+        "value": round(dense_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "experts": cfg.n_experts, "hidden": cfg.hidden, "ffn": cfg.ffn,
+                   "tokens": cfg.tokens, "top_k": cfg.top_k, "experts_materialized_per_step": int(n_fit),
+                   "block_bytes": 4096, "step": "materialize + expert FFN on one stream"},
+        "roofline": {"kernel": "decode_kernel", "bound": "hbm", "achieved": round(achieved, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic, "algorithmic_bytes_per_launch": comp_bytes + dense_bytes,
+                     "avg_launch_ms": round(decode_ms, 4)},
+        "materialize": {"dense_out_GBps": round(dense_bytes / (decode_ms * 1e-3) / 1e9, 1),
+                        "compressed_bytes": comp_bytes, "dense_bytes": dense_bytes,
+                        "compressed_over_dense": round(comp_bytes / dense_bytes, 4),
+                        "payload_saving": round(1 - (8 + (info.payload_bits[0] + info.payload_bits[1]) /
+                                                     (info.elements[0] + info.elements[1])) / 16, 4)},
+        "ffn": {"TFLOPs": round(flops / (ffn_ms * 1e-3) / 1e12, 2), "ms": round(ffn_ms, 4),
+                "frac_mfma_peak": round(flops / (ffn_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                "weight_stream_GBps": round(dense_bytes / (ffn_ms * 1e-3) / 1e9, 1),
+                "frac_hbm_peak": round(dense_bytes / (ffn_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                "pairs": pairs,
+                "kernels_ms": {k: round(prof[k][0] / max(1, prof[k][1]), 4)
+                               for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")}},
+        "setup_s": round(setup_s, 1),
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(pool, cfg, blob, w13, w2, args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+    pool.close()
+
+
+def cpu_baseline(pool, cfg, blob, w13, w2, budget_s):
+    """The oracle decoder, as it stands, on a bounded sample of the same pool (rank 0, host)."""
+    import numpy as np
+    from oracle import codec
+    from paper_2604_02715_amd import binding as B
+    from paper_2604_02715_amd import inputs
+
+    blocks = blob.numpy().reshape(-1, 4096)
+    b0, nb = B.fluxmoe_tensor_blocks(pool.ctx, 0, 2, 0)
+    lens = B.fluxmoe_code_lengths(pool.ctx, 0, 2)
+    first = B.fluxmoe_tensor_first_elems(pool.ctx, 0, 2, 0)
+    want = inputs.bits_u16(w2[0]).reshape(-1)
+    chunk = 256
+    done_blocks, elems = 0, 0
+    t0 = time.perf_counter()
+    while done_blocks < nb and time.perf_counter() - t0 < budget_s:
+        k = min(chunk, nb - done_blocks)
+        e0, n, parts = codec.decode_blocks(blocks[b0 + done_blocks:b0 + done_blocks + k], lens)
+        for a, cnt, p in zip(e0, n, parts):
+            assert np.array_equal(p, want[a:a + cnt]), "oracle decode mismatch"
+            elems += int(cnt)
+        done_blocks += k
+    dt = time.perf_counter() - t0
+    assert elems == int(first[done_blocks]) - int(first[0])
+    return {"value": round(2.0 * elems / dt / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "oracle/codec.decode_blocks on the first %d of %d blocks of expert 0's down "
+                      "tensor of this pool (%d elements, %.1f s, numpy, one thread)"
+                      % (done_blocks, nb, elems, dt)}
+
+
+if __name__ == "__main__":
+    main()

@@ -216,6 +216,18 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* ctx, uint32_t layer, const uint16_t* tokens,
                        const int32_t* topk_ids, const float* topk_w, uint32_t K,
                        const int32_t* page_table, float* out, uint32_t flags, void* stream);
 
+/*
+ * Kernel timing for benchmarks.  While enabled, every kernel the library launches is
+ * bracketed by HIP events on its own stream.  fluxmoe_profile_collect waits for them, adds
+ * the elapsed milliseconds and launch counts per kind and forgets them:
+ *   kind 0 decode + paged scatter, 1 token grouping, 2 gate/up product + SwiGLU,
+ *   3 down product, 4 gated combine.
+ */
+#define FLUXMOE_PROFILE_KINDS 5
+int fluxmoe_profile_enable(fluxmoe_ctx* ctx, int on);
+int fluxmoe_profile_collect(fluxmoe_ctx* ctx, double out_ms[FLUXMOE_PROFILE_KINDS],
+                            uint32_t out_count[FLUXMOE_PROFILE_KINDS]);
+
 /* Synchronous: read and clear the device error word (0 = none; bit 0 a block failed
  * validation during decode and was skipped, bit 1 an unmapped expert was routed to). */
 int fluxmoe_device_errors(fluxmoe_ctx* ctx, uint32_t* out_flags);

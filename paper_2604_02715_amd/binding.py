@@ -68,6 +68,8 @@ EXPORTS = {
     "fluxmoe_expert_ffn": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
                                      C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
                                      C.c_void_p]),
+    "fluxmoe_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
+    "fluxmoe_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]),
     "fluxmoe_device_errors": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
 }
 
@@ -192,6 +194,21 @@ def fluxmoe_expert_ffn(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K, p
                        out_ptr, flags=0, stream=None):
     _check(lib().fluxmoe_expert_ffn(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K,
                                     page_table_ptr, out_ptr, flags, stream))
+
+
+PROFILE_KINDS = ("decode", "grouping", "gemm1_swiglu", "gemm2", "combine")
+
+
+def fluxmoe_profile_enable(ctx, on: bool):
+    _check(lib().fluxmoe_profile_enable(ctx, int(on)))
+
+
+def fluxmoe_profile_collect(ctx) -> dict:
+    """{kind: (total_ms, launches)} since the last collect."""
+    ms = (C.c_double * 5)()
+    cnt = (C.c_uint32 * 5)()
+    _check(lib().fluxmoe_profile_collect(ctx, ms, cnt))
+    return {k: (float(ms[i]), int(cnt[i])) for i, k in enumerate(PROFILE_KINDS)}
 
 
 def fluxmoe_device_errors(ctx) -> int:

@@ -342,29 +342,31 @@ __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
 
 }  // namespace
 
-hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream) {
+hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook hook, void* user) {
     (void)n_cus;
     if (a.T == 0) return hipSuccess;
+    auto mark = [&](int kind, int begin) { if (hook) hook(user, kind, begin, stream); };
     const size_t sh = (2 * size_t(a.E) + 1024) * sizeof(int32_t);
+    mark(1, 1);
     hipLaunchKernelGGL(route_sort_kernel, dim3(1), dim3(1024), sh, stream, a);
+    mark(1, 0);
     const uint32_t strips1 = (a.F + kStrip - 1) / kStrip;
     const uint32_t strips2 = (a.H + kStrip - 1) / kStrip;
     const dim3 g1((strips1 + 3) / 4, a.tiles_cap, 1);
     const dim3 g2((strips2 + 3) / 4, a.tiles_cap, a.ksplit);
-    switch (a.m_tile) {
-        case 16:
-            hipLaunchKernelGGL(gemm1_swiglu_kernel<1>, g1, dim3(256), 0, stream, a);
-            hipLaunchKernelGGL(gemm2_kernel<1>, g2, dim3(256), 0, stream, a);
-            break;
-        case 32:
-            hipLaunchKernelGGL(gemm1_swiglu_kernel<2>, g1, dim3(256), 0, stream, a);
-            hipLaunchKernelGGL(gemm2_kernel<2>, g2, dim3(256), 0, stream, a);
-            break;
-        default:
-            return hipErrorInvalidValue;
-    }
+    if (a.m_tile != 16 && a.m_tile != 32) return hipErrorInvalidValue;
+    mark(2, 1);
+    if (a.m_tile == 16) hipLaunchKernelGGL(gemm1_swiglu_kernel<1>, g1, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(gemm1_swiglu_kernel<2>, g1, dim3(256), 0, stream, a);
+    mark(2, 0);
+    mark(3, 1);
+    if (a.m_tile == 16) hipLaunchKernelGGL(gemm2_kernel<1>, g2, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(gemm2_kernel<2>, g2, dim3(256), 0, stream, a);
+    mark(3, 0);
     const dim3 gc((a.H / 4 + 255) / 256, a.T, 1);
+    mark(4, 1);
     hipLaunchKernelGGL(combine_kernel, gc, dim3(256), 0, stream, a);
+    mark(4, 0);
     return hipGetLastError();
 }
 

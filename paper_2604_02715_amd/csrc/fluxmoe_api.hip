@@ -92,6 +92,10 @@ struct fluxmoe_ctx {
     std::vector<hipEvent_t> ev_copied;
     hipEvent_t ev_half_done[2] = {};
     bool half_done_valid[2] = {false, false};
+    // optional kernel timing (fluxmoe_profile_*)
+    bool profiling = false;
+    struct Span { hipEvent_t a, b; int kind; };
+    std::vector<Span> spans;
 };
 
 namespace {
@@ -186,6 +190,27 @@ int ensure_events(fluxmoe_ctx* c) {
                            hipHostMallocDefault));
     c->events_ready = true;
     return FLUXMOE_OK;
+}
+
+hipError_t span_begin(fluxmoe_ctx* c, int kind, hipStream_t s) {
+    if (!c->profiling) return hipSuccess;
+    fluxmoe_ctx::Span sp{nullptr, nullptr, kind};
+    hipError_t e = hipEventCreate(&sp.a);
+    if (e != hipSuccess) return e;
+    e = hipEventCreate(&sp.b);
+    if (e != hipSuccess) return e;
+    c->spans.push_back(sp);
+    return hipEventRecord(sp.a, s);
+}
+
+hipError_t span_end(fluxmoe_ctx* c, hipStream_t s) {
+    if (!c->profiling) return hipSuccess;
+    return hipEventRecord(c->spans.back().b, s);
+}
+
+void ffn_span_hook(void* user, int kind, int begin, hipStream_t s) {
+    fluxmoe_ctx* c = static_cast<fluxmoe_ctx*>(user);
+    if (begin) (void)span_begin(c, kind, s); else (void)span_end(c, s);
 }
 
 }  // namespace
@@ -683,7 +708,9 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
     uint32_t split = uint32_t((uint64_t(n_wg) * cmd->total_blocks[1] + total / 2) / total);
     split = std::min(std::max(split, 1u), n_wg - 1);
     args.wg_split = split;
+    HIPCHECK(span_begin(c, 0, stream));
     HIPCHECK(launch_decode(args, n_wg, waves_per_wg, stream));
+    HIPCHECK(span_end(c, stream));
     HIPCHECK(hipEventRecord(c->ring_ev[slot], stream));
     c->ring_used[slot] = true;
     c->ring_next = (slot + 1) % kRing;
@@ -776,12 +803,35 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, u
     a.pairs_cap = p.pairs_cap; a.tiles_cap = p.tiles_cap; a.m_tile = p.m_tile; a.ksplit = p.ksplit;
 
     if (c->load_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_load[layer], 0));
-    HIPCHECK(launch_ffn(a, c->n_cus, stream));
+    HIPCHECK(launch_ffn(a, c->n_cus, stream, c->profiling ? ffn_span_hook : nullptr, c));
     HIPCHECK(hipEventRecord(c->ev_infer[layer], stream));
     c->infer_valid[layer] = 1;
     const int64_t lo = int64_t(layer) * c->d.n_experts, hi = lo + c->d.n_experts;
     for (uint32_t s = 0; s < c->d.n_slots; ++s)
         if (c->slot_owner[s] >= lo && c->slot_owner[s] < hi) c->slot_last_reader[s] = int32_t(layer);
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_profile_enable(fluxmoe_ctx* c, int on) {
+    if (!c) return set_error(FLUXMOE_EINVAL, "ctx is NULL");
+    c->profiling = on != 0;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_profile_collect(fluxmoe_ctx* c, double out_ms[FLUXMOE_PROFILE_KINDS],
+                            uint32_t out_count[FLUXMOE_PROFILE_KINDS]) {
+    if (!c || !out_ms || !out_count) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    for (int k = 0; k < FLUXMOE_PROFILE_KINDS; ++k) { out_ms[k] = 0; out_count[k] = 0; }
+    for (auto& sp : c->spans) {
+        HIPCHECK(hipEventSynchronize(sp.b));
+        float ms = 0;
+        HIPCHECK(hipEventElapsedTime(&ms, sp.a, sp.b));
+        out_ms[sp.kind] += ms;
+        out_count[sp.kind] += 1;
+        (void)hipEventDestroy(sp.a);
+        (void)hipEventDestroy(sp.b);
+    }
+    c->spans.clear();
     return FLUXMOE_OK;
 }
 

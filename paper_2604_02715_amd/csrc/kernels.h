@@ -87,6 +87,9 @@ struct FfnArgs {
     uint32_t pairs_cap, tiles_cap, m_tile, ksplit;
 };
 
-hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream);
+// hook(user, kind, begin, stream) is called around every kernel when timing is on
+// (kinds: 1 grouping, 2 gate/up product + SwiGLU, 3 down product, 4 combine)
+typedef void (*SpanHook)(void* user, int kind, int begin, hipStream_t stream);
+hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHook hook, void* user);
 
 }  // namespace fluxmoe
