@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain 1 GiB device copies (known traffic) and report their rate; "
+                         "under rocprofv3 --pmc they calibrate FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); "
@@ -90,6 +93,22 @@ def main():
             ref = w2[int(e)].reshape(-1).view(torch.int16).cuda()
             assert torch.equal(pool.slot2(int(s)), ref), "decode mismatch"
         del ref
+
+    copy_gbps = None
+    if args.copy_calibration:
+        n = 1 << 29                                   # 1 GiB of int16
+        src = torch.arange(n, dtype=torch.int32, device="cuda").to(torch.int16)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        ev1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 5 * 2 * (2 * n) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -151,6 +170,8 @@ def main():
                                for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")}},
         "setup_s": round(setup_s, 1),
     }
+    if copy_gbps is not None:
+        result["device_copy_GBps"] = round(copy_gbps, 1)      # read + write bytes of a plain copy
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(pool, cfg, blob, w13, w2, args.cpu_seconds)

@@ -217,6 +217,15 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* ctx, uint32_t layer, const uint16_t* tokens,
                        const int32_t* page_table, float* out, uint32_t flags, void* stream);
 
 /*
+ * Measurement aid: a plain device-to-device copy of `bytes` bytes (multiple of 16, both
+ * pointers 16-byte aligned) with the same streaming 16-byte accesses the decode kernel
+ * uses, on n_workgroups workgroups of 256 lanes.  Gives the achievable HBM rate on the box
+ * and a known-traffic kernel for calibrating hardware counters.  Needs no context.
+ */
+int fluxmoe_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_workgroups,
+                        void* stream);
+
+/*
  * Kernel timing for benchmarks.  While enabled, every kernel the library launches is
  * bracketed by HIP events on its own stream.  fluxmoe_profile_collect waits for them, adds
  * the elapsed milliseconds and launch counts per kind and forgets them:

@@ -41,18 +41,34 @@ __device__ __forceinline__ uint32_t wave_exclusive_scan(uint32_t v, int lane) {
     return incl - v;
 }
 
-// Decode one pair of symbols.  q is (absolute bit position in the staged block) - 2, with
-// garbage allowed above bit 22.  Returns the two exponent fields packed as BF16 halves.
+// Per-lane bit reservoir: `buf` holds the unread bits of the lane's sub-stream with the next
+// stream bit at bit kShift (the two bits below are don't-care, so a table byte address is one
+// AND away); `cnt` counts valid bits; `k` is the index of the next stream word in the staged
+// block.  Every stream word is fetched from LDS exactly once, and only by the lanes that have
+// run low, which keeps the fetches sparse and mostly free of bank conflicts.
+constexpr uint32_t kShift = 2;
+constexpr uint32_t kRefillBelow = 25;   // a pair needs at most 24 bits; 24 + 32 + kShift <= 64
+
+struct Reservoir {
+    uint64_t buf;
+    uint32_t cnt;
+    uint32_t k;
+};
+
+// Decode one pair of symbols; returns the two exponent fields packed as BF16 halves.
 __device__ __forceinline__ uint32_t decode_pair(const uint32_t* __restrict__ stage,
-                                                const uint32_t* __restrict__ lut, uint32_t& q) {
-    const uint32_t widx = (q >> 5) & (kBlockWords - 1);
-    const uint32_t w0 = stage[widx];
-    const uint32_t w1 = stage[widx + 1];
-    uint32_t win = __builtin_amdgcn_alignbit(w1, w0, q);   // ({w1,w0} >> (q & 31))
-    const uint32_t e0 = lut[(win >> 2) & (kLutEntries - 1)];
-    win >>= (e0 & 31u);
-    const uint32_t e1 = lut[(win >> 2) & (kLutEntries - 1)];
-    q += e0 + e1;
+                                                const uint32_t* __restrict__ lut, Reservoir& r) {
+    if (r.cnt < kRefillBelow) {
+        const uint64_t w = stage[r.k & (kBlockWords - 1)];
+        r.buf |= w << (r.cnt + kShift);
+        r.cnt += 32;
+        r.k += 1;
+    }
+    const uint32_t e0 = lut[(uint32_t(r.buf) >> kShift) & (kLutEntries - 1)];
+    r.buf >>= (e0 & 63u);
+    const uint32_t e1 = lut[(uint32_t(r.buf) >> kShift) & (kLutEntries - 1)];
+    r.buf >>= (e1 & 63u);
+    r.cnt -= (e0 + e1) & 31u;
     // bytes: [e0.b2, e0.b3, e1.b2, e1.b3]
     return __builtin_amdgcn_perm(e1, e0, 0x07060302u);
 }
@@ -96,30 +112,38 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(DecodeArgs a) {
     }
     __syncthreads();
 
+    // Blocks are dealt to wavefronts in chunks of a.chunk_blocks, round-robin over all
+    // wavefronts of this tensor type: at any moment the grid works on one contiguous window
+    // of the pool and of the slots, which HBM serves better than thousands of far-apart
+    // sequential streams.
     const uint32_t n_waves = wg_count * WAVES;
     const uint32_t my_wave = (blockIdx.x - wg_first) * WAVES + wave;
-    const uint32_t per = (total + n_waves - 1) / n_waves;
-    uint32_t b = my_wave * per;
-    const uint32_t b_end = min(total, b + per);
-    if (b >= b_end) return;
+    const uint32_t chunk = a.chunk_blocks;
+    if (uint64_t(my_wave) * chunk >= total) return;
 
-    // job that contains block b: last j with jobs[j].first_block <= b
-    uint32_t lo = 0, hi = n_jobs - 1;
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi + 1) >> 1;
-        if (jobs[mid].first_block <= b) lo = mid; else hi = mid - 1;
-    }
-    uint32_t j = lo;
-    DecodeJob job = jobs[j];
-
+    uint32_t j = 0;
+    DecodeJob job = jobs[0];
     uint32_t* stage = stage_all[wave];
-    for (; b < b_end; ++b) {
+    for (uint64_t c0 = uint64_t(my_wave) * chunk; c0 < total; c0 += uint64_t(n_waves) * chunk) {
+      const uint32_t b_end = uint32_t(min(uint64_t(total), c0 + chunk));
+      uint32_t b = uint32_t(c0);
+      if (b >= job.first_block + job.n_blocks) {
+        // job that contains block b: last index with first_block <= b (jobs are ascending)
+        uint32_t lo = j + 1, hi = n_jobs - 1;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi + 1) >> 1;
+            if (jobs[mid].first_block <= b) lo = mid; else hi = mid - 1;
+        }
+        j = lo;
+        job = jobs[j];
+      }
+      for (; b < b_end; ++b) {
         while (b >= job.first_block + job.n_blocks) job = jobs[++j];
-        const uint4* src = reinterpret_cast<const uint4*>(job.src + uint64_t(b - job.first_block) * 4096u);
-        const uint4 v0 = load_stream16(src + lane);
-        const uint4 v1 = load_stream16(src + lane + 64);
-        const uint4 v2 = load_stream16(src + lane + 128);
-        const uint4 v3 = load_stream16(src + lane + 192);
+        const char* src = reinterpret_cast<const char*>(job.src + uint64_t(b - job.first_block) * 4096u);
+        const uint4 v0 = load_stream16(src + 16 * lane);
+        const uint4 v1 = load_stream16(src + 16 * lane + 1024);
+        const uint4 v2 = load_stream16(src + 16 * lane + 2048);
+        const uint4 v3 = load_stream16(src + 16 * lane + 3072);
         uint4* st4 = reinterpret_cast<uint4*>(stage);
         st4[lane] = v0;
         st4[lane + 64] = v1;
@@ -139,7 +163,11 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(DecodeArgs a) {
             if (lane == 0) atomicOr(a.error_word, 1u);
             continue;
         }
-        uint32_t q = (kHeaderBytes + n) * 8u + start - 2u;
+        const uint32_t p0 = (kHeaderBytes + n) * 8u + start;     // first bit of this lane's sub-stream
+        Reservoir q;
+        q.k = (p0 >> 5) + 1;
+        q.cnt = 32u - (p0 & 31u);
+        q.buf = uint64_t(stage[p0 >> 5] >> (p0 & 31u)) << kShift;
         const uint32_t n_runs = n >> 3;
         uint16_t* out = reinterpret_cast<uint16_t*>(job.dst) + e0;
         for (uint32_t r = lane; r < n_runs; r += 64) {
@@ -156,6 +184,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(DecodeArgs a) {
             o.w = join_pair(x3, sm_hi, 0x03030202u);
             store_stream16(out + 8u * r, o);
         }
+      }
     }
 }
 
@@ -191,6 +220,25 @@ hipError_t launch_apply_updates(int32_t* page_table, const void* upd, uint32_t n
     if (n == 0) return hipSuccess;
     hipLaunchKernelGGL(apply_updates_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, page_table,
                        static_cast<const int2*>(upd), n);
+    return hipGetLastError();
+}
+
+namespace {
+// Plain streaming copy with the same 16-byte non-temporal accesses the decode kernel uses:
+// the reference point for achievable HBM bandwidth and for hardware-counter calibration.
+__global__ __launch_bounds__(256) void stream_copy_kernel(const uint4* __restrict__ src,
+                                                          uint4* __restrict__ dst, uint64_t n16) {
+    const uint64_t stride = uint64_t(gridDim.x) * 256;
+    for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += stride)
+        store_stream16(dst + i, load_stream16(src + i));
+}
+}  // namespace
+
+hipError_t launch_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_workgroups,
+                              hipStream_t stream) {
+    if (bytes < 16) return hipSuccess;
+    hipLaunchKernelGGL(stream_copy_kernel, dim3(n_workgroups), dim3(256), 0, stream,
+                       static_cast<const uint4*>(src), static_cast<uint4*>(dst), bytes / 16);
     return hipGetLastError();
 }
 

@@ -129,8 +129,6 @@ __device__ __forceinline__ uint32_t comp(const uint4& v, int i) {
 template <int MI, int NMAT>
 struct StripGemm {
     f32x4 acc[MI][8][NMAT];
-    uint4 bv[NMAT][8];
-    uint4 av[MI];
 
     __device__ __forceinline__ void zero() {
 #pragma unroll
@@ -141,63 +139,103 @@ struct StripGemm {
                 for (int m = 0; m < NMAT; ++m) acc[mi][c][m] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // lane's rows k0..k0+7 of the B strip (its 8 columns must exist) and its A fragments
-    // (a lane's A row is independent of its B columns); k_ok = k0 inside the k range
-    __device__ __forceinline__ void load(const uint16_t* const (&arow)[MI], const uint16_t* bcol,
-                                         size_t ldb, size_t mat_stride, uint32_t k0, bool k_ok,
-                                         bool col_ok) {
-        const bool ok = k_ok && col_ok;
-        const uint4 z = make_uint4(0, 0, 0, 0);
+    // the lane's 8 rows k0..k0+7 of one matrix of the B strip
+    __device__ __forceinline__ static void load_b(uint4 (&bv)[8], const uint16_t* bcol, size_t ldb,
+                                                  uint32_t k0) {
 #pragma unroll
-        for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-            for (int r = 0; r < 8; ++r)
-                bv[m][r] = ok ? load_stream16(bcol + m * mat_stride + size_t(k0 + r) * ldb) : z;
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-            av[mi] = k_ok ? *reinterpret_cast<const uint4*>(arow[mi] + k0) : z;
+        for (int r = 0; r < 8; ++r) bv[r] = load_stream16(bcol + size_t(k0 + r) * ldb);
     }
 
-    __device__ __forceinline__ void mma(const uint4 (&b)[NMAT][8], const uint4 (&a)[MI]) {
+    // the lane's A fragments
+    __device__ __forceinline__ static void load_a(uint4 (&av)[MI], const uint16_t* const (&arow)[MI],
+                                                  uint32_t k0) {
 #pragma unroll
-        for (int m = 0; m < NMAT; ++m)
+        for (int mi = 0; mi < MI; ++mi) av[mi] = *reinterpret_cast<const uint4*>(arow[mi] + k0);
+    }
+
+    template <int M>
+    __device__ __forceinline__ void mma(const uint4 (&b)[8], const uint4 (&a)[MI]) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                Frag f;
-                const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-                f.u.x = __builtin_amdgcn_perm(comp(b[m][1], c >> 1), comp(b[m][0], c >> 1), sel);
-                f.u.y = __builtin_amdgcn_perm(comp(b[m][3], c >> 1), comp(b[m][2], c >> 1), sel);
-                f.u.z = __builtin_amdgcn_perm(comp(b[m][5], c >> 1), comp(b[m][4], c >> 1), sel);
-                f.u.w = __builtin_amdgcn_perm(comp(b[m][7], c >> 1), comp(b[m][6], c >> 1), sel);
+        for (int c = 0; c < 8; ++c) {
+            Frag f;
+            const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+            f.u.x = __builtin_amdgcn_perm(comp(b[1], c >> 1), comp(b[0], c >> 1), sel);
+            f.u.y = __builtin_amdgcn_perm(comp(b[3], c >> 1), comp(b[2], c >> 1), sel);
+            f.u.z = __builtin_amdgcn_perm(comp(b[5], c >> 1), comp(b[4], c >> 1), sel);
+            f.u.w = __builtin_amdgcn_perm(comp(b[7], c >> 1), comp(b[6], c >> 1), sel);
 #pragma unroll
-                for (int mi = 0; mi < MI; ++mi) {
-                    Frag fa;
-                    fa.u = a[mi];
-                    acc[mi][c][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v, f.v, acc[mi][c][m], 0, 0, 0);
-                }
+            for (int mi = 0; mi < MI; ++mi) {
+                Frag fa;
+                fa.u = a[mi];
+                acc[mi][c][M] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v, f.v, acc[mi][c][M], 0, 0, 0);
             }
+        }
     }
 
-    // C = A[rows][k_begin:k_end] * B[k_begin:k_end][strip]; k range multiple of 8
+    // C = A[rows][k_begin:k_end] * B[k_begin:k_end][strip] for each of the NMAT matrices
+    // (matrix m starts mat_stride elements after matrix 0); k range a multiple of 8.  bcol
+    // must point at 8 existing columns for every lane (callers clamp lanes past the edge).
+    // Software pipeline over (k chunk, matrix) stages: the next stage's rows are in flight
+    // while the current stage's MFMAs run.  A k range that is not a multiple of 32 ends with
+    // one chunk in which the lanes past the end contribute zeros.
     __device__ __forceinline__ void run(const uint16_t* const (&arow)[MI], const uint16_t* bcol,
                                         size_t ldb, size_t mat_stride, uint32_t k_begin,
-                                        uint32_t k_end, bool col_ok, int lane) {
+                                        uint32_t k_end, int lane) {
         zero();
         const uint32_t kg = 8u * (uint32_t(lane) >> 4);
-        uint32_t k0 = k_begin + kg;
-        load(arow, bcol, ldb, mat_stride, k0, k0 < k_end, col_ok);
-        for (uint32_t kc = k_begin; kc < k_end; kc += kChunk) {
-            uint4 bcur[NMAT][8];
-            uint4 acur[MI];
-#pragma unroll
-            for (int m = 0; m < NMAT; ++m)
-#pragma unroll
-                for (int r = 0; r < 8; ++r) bcur[m][r] = bv[m][r];
-#pragma unroll
-            for (int mi = 0; mi < MI; ++mi) acur[mi] = av[mi];
+        const uint32_t k_full = k_begin + (k_end - k_begin) / kChunk * kChunk;
+        uint4 b0[8], b1[8], a0[MI], a1[MI];
+        if (k_begin < k_full) {
+            load_a(a0, arow, k_begin + kg);
+            load_b(b0, bcol, ldb, k_begin + kg);
+        }
+        for (uint32_t kc = k_begin; kc < k_full; kc += kChunk) {
             const uint32_t kn = kc + kChunk + kg;
-            if (kc + kChunk < k_end) load(arow, bcol, ldb, mat_stride, kn, kn < k_end, col_ok);
-            mma(bcur, acur);
+            const bool more = kc + kChunk < k_full;
+            if (NMAT == 2) {
+                load_b(b1, bcol + mat_stride, ldb, kc + kg);
+                mma<0>(b0, a0);
+                if (more) {
+                    load_a(a1, arow, kn);
+                    load_b(b0, bcol, ldb, kn);
+                }
+                mma<NMAT - 1>(b1, a0);
+                if (more) {
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi) a0[mi] = a1[mi];
+                }
+            } else {
+                if (more) {
+                    load_a(a1, arow, kn);
+                    load_b(b1, bcol, ldb, kn);
+                }
+                mma<0>(b0, a0);
+                if (more) {
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) b0[r] = b1[r];
+#pragma unroll
+                    for (int mi = 0; mi < MI; ++mi) a0[mi] = a1[mi];
+                }
+            }
+        }
+        if (k_full < k_end) {
+            const uint4 z = make_uint4(0, 0, 0, 0);
+            const bool ok = k_full + kg < k_end;
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) a0[mi] = z;
+#pragma unroll
+            for (int r = 0; r < 8; ++r) b0[r] = z;
+            if (ok) {
+                load_a(a0, arow, k_full + kg);
+                load_b(b0, bcol, ldb, k_full + kg);
+            }
+            mma<0>(b0, a0);
+            if (NMAT == 2) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) b1[r] = z;
+                if (ok) load_b(b1, bcol + mat_stride, ldb, k_full + kg);
+                mma<NMAT - 1>(b1, a0);
+            }
         }
     }
 };
@@ -246,7 +284,7 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
     const uint16_t* w13 = a.slots13 + size_t(t.slot) * 2 * mat;
 
     StripGemm<MI, 2> g;
-    g.run(arow, w13 + n0, a.F, mat, 0, a.H, col_ok, lane);
+    g.run(arow, w13 + (col_ok ? n0 : a.F - 8), a.F, mat, 0, a.H, lane);
 
     if (!col_ok) return;
 #pragma unroll
@@ -297,7 +335,7 @@ __global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
     const uint16_t* w2 = a.slots2 + size_t(t.slot) * a.F * a.H;
 
     StripGemm<MI, 1> g;
-    g.run(arow, w2 + n0, a.H, 0, k_begin, k_end, col_ok, lane);
+    g.run(arow, w2 + (col_ok ? n0 : a.H - 8), a.H, 0, k_begin, k_end, lane);
 
     if (!col_ok) return;
     float* y = a.ybuf + size_t(split) * a.pairs_cap * a.H;
@@ -354,14 +392,16 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
     const uint32_t strips2 = (a.H + kStrip - 1) / kStrip;
     const dim3 g1((strips1 + 3) / 4, a.tiles_cap, 1);
     const dim3 g2((strips2 + 3) / 4, a.tiles_cap, a.ksplit);
-    if (a.m_tile != 16 && a.m_tile != 32) return hipErrorInvalidValue;
+    if (a.m_tile != 16 && a.m_tile != 32 && a.m_tile != 64) return hipErrorInvalidValue;
     mark(2, 1);
     if (a.m_tile == 16) hipLaunchKernelGGL(gemm1_swiglu_kernel<1>, g1, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(gemm1_swiglu_kernel<2>, g1, dim3(256), 0, stream, a);
+    else if (a.m_tile == 32) hipLaunchKernelGGL(gemm1_swiglu_kernel<2>, g1, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(gemm1_swiglu_kernel<4>, g1, dim3(256), 0, stream, a);
     mark(2, 0);
     mark(3, 1);
     if (a.m_tile == 16) hipLaunchKernelGGL(gemm2_kernel<1>, g2, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(gemm2_kernel<2>, g2, dim3(256), 0, stream, a);
+    else if (a.m_tile == 32) hipLaunchKernelGGL(gemm2_kernel<2>, g2, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(gemm2_kernel<4>, g2, dim3(256), 0, stream, a);
     mark(3, 0);
     const dim3 gc((a.H / 4 + 255) / 256, a.T, 1);
     mark(4, 1);

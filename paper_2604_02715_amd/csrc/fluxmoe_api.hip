@@ -11,6 +11,7 @@
 #include <algorithm>
 #include <array>
 #include <atomic>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <thread>
@@ -92,6 +93,10 @@ struct fluxmoe_ctx {
     std::vector<hipEvent_t> ev_copied;
     hipEvent_t ev_half_done[2] = {};
     bool half_done_valid[2] = {false, false};
+    // launch shape of the decode kernel (FLUXMOE_DECODE_WAVES / FLUXMOE_DECODE_WG_PER_CU override)
+    int tune_waves = 16;
+    int tune_wg_per_cu = 8;
+    int tune_chunk = 1;
     // optional kernel timing (fluxmoe_profile_*)
     bool profiling = false;
     struct Span { hipEvent_t a, b; int kind; };
@@ -118,7 +123,7 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
     const uint64_t pairs = uint64_t(T) * K;
     const uint64_t groups = std::max<uint64_t>(1, std::min<uint64_t>(E, pairs));
     const uint64_t avg = (pairs + groups - 1) / groups;
-    p.m_tile = avg > 16 ? 32 : 16;
+    p.m_tile = avg > 32 ? 64 : (avg > 16 ? 32 : 16);
     p.pairs_cap = uint32_t(std::max<uint64_t>(pairs, 1));
     p.tiles_cap = uint32_t(pairs / p.m_tile + groups + 1);
     // split K of the second product until about 8 wavefronts per CU have work
@@ -248,6 +253,18 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     c->infer_valid.assign(d.n_layers, 0);
     c->stage.resize(d.n_layers);
     compute_layout(c);
+    if (const char* v = std::getenv("FLUXMOE_DECODE_WAVES")) {
+        const int w = std::atoi(v);
+        if (w == 4 || w == 8 || w == 16) c->tune_waves = w;
+    }
+    if (const char* v = std::getenv("FLUXMOE_DECODE_CHUNK")) {
+        const int w = std::atoi(v);
+        if (w >= 1 && w <= (1 << 20)) c->tune_chunk = w;
+    }
+    if (const char* v = std::getenv("FLUXMOE_DECODE_WG_PER_CU")) {
+        const int w = std::atoi(v);
+        if (w >= 1 && w <= 64) c->tune_wg_per_cu = w;
+    }
     *out_ctx = c;
     g_err[0] = 0;
     return FLUXMOE_OK;
@@ -701,13 +718,14 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
     args.lut[1] = reinterpret_cast<const uint32_t*>(c->ws + c->lut_off + (uint64_t(layer) * 2 + 1) * kLutBytes);
     args.page_table = page_table;
     args.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
-    const int waves_per_wg = 8;
+    const int waves_per_wg = c->tune_waves;
     const uint64_t total = uint64_t(cmd->total_blocks[0]) + cmd->total_blocks[1];
-    uint32_t n_wg = uint32_t(std::min<uint64_t>(uint64_t(c->n_cus) * 3, (total + waves_per_wg - 1) / waves_per_wg));
+    uint32_t n_wg = uint32_t(std::min<uint64_t>(uint64_t(c->n_cus) * c->tune_wg_per_cu, (total + waves_per_wg - 1) / waves_per_wg));
     n_wg = std::max(n_wg, 2u);
     uint32_t split = uint32_t((uint64_t(n_wg) * cmd->total_blocks[1] + total / 2) / total);
     split = std::min(std::max(split, 1u), n_wg - 1);
     args.wg_split = split;
+    args.chunk_blocks = uint32_t(c->tune_chunk);
     HIPCHECK(span_begin(c, 0, stream));
     HIPCHECK(launch_decode(args, n_wg, waves_per_wg, stream));
     HIPCHECK(span_end(c, stream));
@@ -809,6 +827,14 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, u
     const int64_t lo = int64_t(layer) * c->d.n_experts, hi = lo + c->d.n_experts;
     for (uint32_t s = 0; s < c->d.n_slots; ++s)
         if (c->slot_owner[s] >= lo && c->slot_owner[s] < hi) c->slot_last_reader[s] = int32_t(layer);
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_workgroups, void* stream) {
+    if (!dst || !src) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    if ((uintptr_t(dst) | uintptr_t(src) | bytes) & 15) return set_error(FLUXMOE_EINVAL, "16-byte alignment required");
+    if (n_workgroups == 0 || n_workgroups > (1u << 20)) return set_error(FLUXMOE_EINVAL, "bad n_workgroups");
+    HIPCHECK(launch_stream_copy(dst, src, bytes, n_workgroups, static_cast<hipStream_t>(stream)));
     return FLUXMOE_OK;
 }
 

@@ -15,14 +15,17 @@ constexpr uint32_t kLutEntries = 1u << kLutBits;
 
 #if defined(__HIPCC__)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-// Streaming (non-temporal) 16-byte accesses: data that is touched once.
+typedef __attribute__((address_space(1))) u32x4 global_u32x4;
+// Streaming (non-temporal) 16-byte accesses to device memory: data that is touched once.
+// The pointers are cast to the global address space so that global_load / global_store are
+// emitted instead of flat accesses.
 __device__ __forceinline__ uint4 load_stream16(const void* p) {
-    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    const u32x4 v = __builtin_nontemporal_load((const global_u32x4*)(uintptr_t)p);
     return make_uint4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void store_stream16(void* p, const uint4& v) {
     const u32x4 t = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+    __builtin_nontemporal_store(t, (global_u32x4*)(uintptr_t)p);
 }
 #endif
 
@@ -51,6 +54,7 @@ struct DecodeArgs {
     uint32_t jobs_offset[2];     // byte offsets of the two job lists from cmd
     uint32_t upd_offset;         // byte offset of the int2 (index, value) page-table updates
     uint32_t wg_split;           // workgroups [0, wg_split) decode type 2, the rest type 1
+    uint32_t chunk_blocks;       // consecutive blocks a wavefront takes per round (>= 1)
     const uint32_t* lut[2];      // device decode tables, [0] type 1, [1] type 2
     int32_t* page_table;         // device
     uint32_t* error_word;        // device
@@ -59,6 +63,8 @@ struct DecodeArgs {
 hipError_t launch_decode(const DecodeArgs& args, uint32_t n_workgroups, int waves_per_wg,
                          hipStream_t stream);
 hipError_t launch_fill_i32(int32_t* p, int32_t v, uint64_t n, hipStream_t stream);
+hipError_t launch_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_workgroups,
+                              hipStream_t stream);
 // page_table[upd[i].x] = upd[i].y for i < n (upd: device int2 list)
 hipError_t launch_apply_updates(int32_t* page_table, const void* upd, uint32_t n, hipStream_t stream);
 
