@@ -23,11 +23,15 @@ import numpy as np
 
 class PagedSlots:
     def __init__(self, n_layers: int, n_experts: int, n_slots: int, hidden: int, ffn: int,
-                 poison: int = 0x7FC1):
+                 poison: int = 0x7FC1, track_bytes: bool = True):
+        """track_bytes=False models only the page table and slot ownership (full-size layers,
+        where the slot contents are compared on the device against the original tensors)."""
         self.n13 = 2 * hidden * ffn              # elements of a fused gate/up tensor
         self.n2 = hidden * ffn                   # elements of a down tensor
-        self.slots13 = np.full((n_slots, self.n13), poison, dtype=np.uint16)
-        self.slots2 = np.full((n_slots, self.n2), poison, dtype=np.uint16)
+        self.track_bytes = track_bytes
+        if track_bytes:
+            self.slots13 = np.full((n_slots, self.n13), poison, dtype=np.uint16)
+            self.slots2 = np.full((n_slots, self.n2), poison, dtype=np.uint16)
         self.page_table = np.full((n_layers, n_experts), -1, dtype=np.int32)
         self.owner = [None] * n_slots            # (layer, expert) or None
 
@@ -44,8 +48,9 @@ class PagedSlots:
             prev = self.owner[s]
             if prev is not None and prev != (layer, e):
                 self.page_table[prev[0], prev[1]] = -1
-            self.slots13[s] = np.asarray(dense13(e), dtype=np.uint16).reshape(-1)
-            self.slots2[s] = np.asarray(dense2(e), dtype=np.uint16).reshape(-1)
+            if self.track_bytes:
+                self.slots13[s] = np.asarray(dense13(e), dtype=np.uint16).reshape(-1)
+                self.slots2[s] = np.asarray(dense2(e), dtype=np.uint16).reshape(-1)
             self.page_table[layer, e] = s
             self.owner[s] = (layer, e)
 

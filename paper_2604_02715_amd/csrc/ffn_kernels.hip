@@ -7,8 +7,8 @@
 //
 //   route_sort   one workgroup: counting sort of the (token, k) pairs by expert, skipping
 //                pairs whose expert has no slot; emits row tiles (expert, first row)
-//   gemm1        per (row tile, 128-column strip): a = X W1, b = X W3 with
-//                v_mfma_f32_16x16x32_bf16, h = silu(a) * b rounded to BF16
+//   gemm1        per (row tile, 128-column strip): a = X W1 and b = X W3 on two wavefronts
+//                with v_mfma_f32_16x16x32_bf16, h = silu(a) * b rounded to BF16
 //   gemm2        per (row tile, 128-column strip, K split): y = h W2, FP32 partial sums
 //   combine      out[t] = sum_k gate[t][k] * sum_splits y[pos(t,k)]   (fixed order)
 //
@@ -126,116 +126,89 @@ __device__ __forceinline__ uint32_t comp(const uint4& v, int i) {
     return i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w));
 }
 
-template <int MI, int NMAT>
+// k chunks per wavefront held in the register ring (one being multiplied, the rest in flight)
+template <int MI> struct RingDepth { static constexpr int value = MI >= 4 ? 3 : 4; };
+
+// One wavefront's product C[16*MI rows][128 columns] = A[rows][k range] * B[k range][strip].
+template <int MI>
 struct StripGemm {
-    f32x4 acc[MI][8][NMAT];
+    f32x4 acc[MI][8];
+
+    struct Stage {
+        uint4 b[8];      // the lane's 8 rows x 8 columns of B
+        uint4 a[MI];     // the lane's A fragments (8 consecutive k of one row per 16-row tile)
+    };
 
     __device__ __forceinline__ void zero() {
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int c = 0; c < 8; ++c)
-#pragma unroll
-                for (int m = 0; m < NMAT; ++m) acc[mi][c][m] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int c = 0; c < 8; ++c) acc[mi][c] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    // the lane's 8 rows k0..k0+7 of one matrix of the B strip
-    __device__ __forceinline__ static void load_b(uint4 (&bv)[8], const uint16_t* bcol, size_t ldb,
-                                                  uint32_t k0) {
+    __device__ __forceinline__ static void load(Stage& st, const uint16_t* const (&arow)[MI],
+                                                const uint16_t* bcol, size_t ldb, uint32_t k0) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) bv[r] = load_stream16(bcol + size_t(k0 + r) * ldb);
+        for (int r = 0; r < 8; ++r) st.b[r] = *reinterpret_cast<const uint4*>(bcol + size_t(k0 + r) * ldb);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) st.a[mi] = *reinterpret_cast<const uint4*>(arow[mi] + k0);
     }
 
-    // the lane's A fragments
-    __device__ __forceinline__ static void load_a(uint4 (&av)[MI], const uint16_t* const (&arow)[MI],
-                                                  uint32_t k0) {
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi) av[mi] = *reinterpret_cast<const uint4*>(arow[mi] + k0);
-    }
-
-    template <int M>
-    __device__ __forceinline__ void mma(const uint4 (&b)[8], const uint4 (&a)[MI]) {
+    __device__ __forceinline__ void mma(const Stage& st) {
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             Frag f;
             const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
-            f.u.x = __builtin_amdgcn_perm(comp(b[1], c >> 1), comp(b[0], c >> 1), sel);
-            f.u.y = __builtin_amdgcn_perm(comp(b[3], c >> 1), comp(b[2], c >> 1), sel);
-            f.u.z = __builtin_amdgcn_perm(comp(b[5], c >> 1), comp(b[4], c >> 1), sel);
-            f.u.w = __builtin_amdgcn_perm(comp(b[7], c >> 1), comp(b[6], c >> 1), sel);
+            f.u.x = __builtin_amdgcn_perm(comp(st.b[1], c >> 1), comp(st.b[0], c >> 1), sel);
+            f.u.y = __builtin_amdgcn_perm(comp(st.b[3], c >> 1), comp(st.b[2], c >> 1), sel);
+            f.u.z = __builtin_amdgcn_perm(comp(st.b[5], c >> 1), comp(st.b[4], c >> 1), sel);
+            f.u.w = __builtin_amdgcn_perm(comp(st.b[7], c >> 1), comp(st.b[6], c >> 1), sel);
 #pragma unroll
             for (int mi = 0; mi < MI; ++mi) {
                 Frag fa;
-                fa.u = a[mi];
-                acc[mi][c][M] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v, f.v, acc[mi][c][M], 0, 0, 0);
+                fa.u = st.a[mi];
+                acc[mi][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v, f.v, acc[mi][c], 0, 0, 0);
             }
         }
     }
 
-    // C = A[rows][k_begin:k_end] * B[k_begin:k_end][strip] for each of the NMAT matrices
-    // (matrix m starts mat_stride elements after matrix 0); k range a multiple of 8.  bcol
-    // must point at 8 existing columns for every lane (callers clamp lanes past the edge).
-    // Software pipeline over (k chunk, matrix) stages: the next stage's rows are in flight
-    // while the current stage's MFMAs run.  A k range that is not a multiple of 32 ends with
-    // one chunk in which the lanes past the end contribute zeros.
+    // k range a multiple of 8.  bcol must point at 8 existing columns for every lane (callers
+    // clamp lanes past the edge).  A ring of 3-4 register stages keeps all but one chunk
+    // of 32 k in flight while that one is multiplied: with one wavefront per SIMD that is what
+    // covers HBM latency.  A k range that is not a multiple of 32 ends with one chunk in
+    // which the lanes past the end contribute zeros.
     __device__ __forceinline__ void run(const uint16_t* const (&arow)[MI], const uint16_t* bcol,
-                                        size_t ldb, size_t mat_stride, uint32_t k_begin,
-                                        uint32_t k_end, int lane) {
+                                        size_t ldb, uint32_t k_begin, uint32_t k_end, int lane) {
+        constexpr int kStages = RingDepth<MI>::value;
         zero();
         const uint32_t kg = 8u * (uint32_t(lane) >> 4);
-        const uint32_t k_full = k_begin + (k_end - k_begin) / kChunk * kChunk;
-        uint4 b0[8], b1[8], a0[MI], a1[MI];
-        if (k_begin < k_full) {
-            load_a(a0, arow, k_begin + kg);
-            load_b(b0, bcol, ldb, k_begin + kg);
-        }
-        for (uint32_t kc = k_begin; kc < k_full; kc += kChunk) {
-            const uint32_t kn = kc + kChunk + kg;
-            const bool more = kc + kChunk < k_full;
-            if (NMAT == 2) {
-                load_b(b1, bcol + mat_stride, ldb, kc + kg);
-                mma<0>(b0, a0);
-                if (more) {
-                    load_a(a1, arow, kn);
-                    load_b(b0, bcol, ldb, kn);
-                }
-                mma<NMAT - 1>(b1, a0);
-                if (more) {
+        const uint32_t n = (k_end - k_begin) / kChunk;
+        const uint32_t kb = k_begin + kg;
+        Stage st[kStages];
 #pragma unroll
-                    for (int mi = 0; mi < MI; ++mi) a0[mi] = a1[mi];
-                }
-            } else {
-                if (more) {
-                    load_a(a1, arow, kn);
-                    load_b(b1, bcol, ldb, kn);
-                }
-                mma<0>(b0, a0);
-                if (more) {
+        for (int s = 0; s < kStages - 1; ++s)
+            if (uint32_t(s) < n) load(st[s], arow, bcol, ldb, kb + s * kChunk);
+        for (uint32_t base = 0; base < n; base += kStages) {
 #pragma unroll
-                    for (int r = 0; r < 8; ++r) b0[r] = b1[r];
-#pragma unroll
-                    for (int mi = 0; mi < MI; ++mi) a0[mi] = a1[mi];
+            for (int s = 0; s < kStages; ++s) {
+                const uint32_t i = base + s;
+                if (i < n) {
+                    if (i + kStages - 1 < n)
+                        load(st[(s + kStages - 1) % kStages], arow, bcol, ldb, kb + (i + kStages - 1) * kChunk);
+                    mma(st[s]);
                 }
             }
         }
+        const uint32_t k_full = k_begin + n * kChunk;
         if (k_full < k_end) {
             const uint4 z = make_uint4(0, 0, 0, 0);
-            const bool ok = k_full + kg < k_end;
+            Stage t;
 #pragma unroll
-            for (int mi = 0; mi < MI; ++mi) a0[mi] = z;
+            for (int mi = 0; mi < MI; ++mi) t.a[mi] = z;
 #pragma unroll
-            for (int r = 0; r < 8; ++r) b0[r] = z;
-            if (ok) {
-                load_a(a0, arow, k_full + kg);
-                load_b(b0, bcol, ldb, k_full + kg);
-            }
-            mma<0>(b0, a0);
-            if (NMAT == 2) {
-#pragma unroll
-                for (int r = 0; r < 8; ++r) b1[r] = z;
-                if (ok) load_b(b1, bcol + mat_stride, ldb, k_full + kg);
-                mma<NMAT - 1>(b1, a0);
-            }
+            for (int r = 0; r < 8; ++r) t.b[r] = z;
+            if (k_full + kg < k_end) load(t, arow, bcol, ldb, k_full + kg);
+            mma(t);
         }
     }
 };
@@ -260,33 +233,48 @@ __device__ __forceinline__ bool tile_info(const FfnArgs& a, uint32_t tile, TileI
     return t.rows > 0 && t.slot >= 0;
 }
 
-// h[row][n] = bf16( silu(x W1) * (x W3) )
+// h[row][n] = bf16( silu(x W1) * (x W3) ).  A workgroup is two pairs of wavefronts; each
+// pair owns one 128-column strip: the even wavefront multiplies by W1 (gate), the odd one by
+// W3 (up), the odd one hands its accumulators over through LDS and the even one applies
+// SwiGLU and stores.  Splitting the two matrices over two wavefronts halves the accumulator
+// registers per wavefront, which is what leaves room for the deep load ring.
 template <int MI>
 __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
+    __shared__ float xch[2][MI * 8 * 4][64];     // [pair][mi, c, r][lane]
     TileInfo t;
-    if (!tile_info(a, blockIdx.y, t)) return;
+    if (!tile_info(a, blockIdx.y, t)) return;     // uniform over the workgroup
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const uint32_t strip = blockIdx.x * 4 + wave;
+    const int pair = wave >> 1;
+    const int mat_id = wave & 1;
+    const uint32_t strip = blockIdx.x * 2 + pair;
     const uint32_t n0 = strip * kStrip + 8u * (lane & 15);
-    if (strip * kStrip >= a.F) return;
-    const bool col_ok = n0 < a.F;
+    const bool col_ok = n0 < a.F;                 // strips past F still run (barrier below)
 
     const uint16_t* arow[MI];
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi) {
         const int32_t r = min(mi * 16 + (lane & 15), t.rows - 1);
-        const int32_t pair = a.sorted_pair[t.row0 + r];
-        const uint32_t tok = uint32_t(pair) / a.K;
+        const int32_t pr = a.sorted_pair[t.row0 + r];
+        const uint32_t tok = uint32_t(pr) / a.K;
         arow[mi] = a.tokens + size_t(tok) * a.H;
     }
     const size_t mat = size_t(a.H) * a.F;
-    const uint16_t* w13 = a.slots13 + size_t(t.slot) * 2 * mat;
+    const uint16_t* w = a.slots13 + size_t(t.slot) * 2 * mat + size_t(mat_id) * mat;
 
-    StripGemm<MI, 2> g;
-    g.run(arow, w13 + (col_ok ? n0 : a.F - 8), a.F, mat, 0, a.H, lane);
+    StripGemm<MI> g;
+    g.run(arow, w + (col_ok ? n0 : a.F - 8), a.F, 0, a.H, lane);
 
-    if (!col_ok) return;
+    if (mat_id == 1) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int c = 0; c < 8; ++c)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) xch[pair][(mi * 8 + c) * 4 + r][lane] = g.acc[mi][c][r];
+    }
+    __syncthreads();
+    if (mat_id == 1 || !col_ok) return;
 #pragma unroll
     for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -296,8 +284,8 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
             uint32_t hb[8];
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
-                const float ga = g.acc[mi][c][0][r];
-                const float up = g.acc[mi][c][1][r];
+                const float ga = g.acc[mi][c][r];
+                const float up = xch[pair][(mi * 8 + c) * 4 + r][lane];
                 const float h = ga / (1.0f + __expf(-ga)) * up;
                 hb[c] = f32_to_bf16_rne(h);
             }
@@ -334,8 +322,8 @@ __global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
     }
     const uint16_t* w2 = a.slots2 + size_t(t.slot) * a.F * a.H;
 
-    StripGemm<MI, 1> g;
-    g.run(arow, w2 + (col_ok ? n0 : a.H - 8), a.H, 0, k_begin, k_end, lane);
+    StripGemm<MI> g;
+    g.run(arow, w2 + (col_ok ? n0 : a.H - 8), a.H, k_begin, k_end, lane);
 
     if (!col_ok) return;
     float* y = a.ybuf + size_t(split) * a.pairs_cap * a.H;
@@ -345,10 +333,8 @@ __global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
         for (int r = 0; r < 4; ++r) {
             const int32_t row = mi * 16 + 4 * (lane >> 4) + r;
             if (row >= t.rows) continue;
-            float4 lo = make_float4(g.acc[mi][0][0][r], g.acc[mi][1][0][r], g.acc[mi][2][0][r],
-                                    g.acc[mi][3][0][r]);
-            float4 hi = make_float4(g.acc[mi][4][0][r], g.acc[mi][5][0][r], g.acc[mi][6][0][r],
-                                    g.acc[mi][7][0][r]);
+            float4 lo = make_float4(g.acc[mi][0][r], g.acc[mi][1][r], g.acc[mi][2][r], g.acc[mi][3][r]);
+            float4 hi = make_float4(g.acc[mi][4][r], g.acc[mi][5][r], g.acc[mi][6][r], g.acc[mi][7][r]);
             float4* dst = reinterpret_cast<float4*>(y + size_t(t.row0 + row) * a.H + n0);
             dst[0] = lo;
             dst[1] = hi;
@@ -390,7 +376,7 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
     mark(1, 0);
     const uint32_t strips1 = (a.F + kStrip - 1) / kStrip;
     const uint32_t strips2 = (a.H + kStrip - 1) / kStrip;
-    const dim3 g1((strips1 + 3) / 4, a.tiles_cap, 1);
+    const dim3 g1((strips1 + 1) / 2, a.tiles_cap, 1);
     const dim3 g2((strips2 + 3) / 4, a.tiles_cap, a.ksplit);
     if (a.m_tile != 16 && a.m_tile != 32 && a.m_tile != 64) return hipErrorInvalidValue;
     mark(2, 1);
