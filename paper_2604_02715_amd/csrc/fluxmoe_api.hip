@@ -124,6 +124,10 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
     const uint64_t groups = std::max<uint64_t>(1, std::min<uint64_t>(E, pairs));
     const uint64_t avg = (pairs + groups - 1) / groups;
     p.m_tile = avg > 32 ? 64 : (avg > 16 ? 32 : 16);
+    if (const char* v = std::getenv("FLUXMOE_FFN_MTILE")) {
+        const int m = std::atoi(v);
+        if (m == 16 || m == 32 || m == 64) p.m_tile = uint32_t(m);
+    }
     p.pairs_cap = uint32_t(std::max<uint64_t>(pairs, 1));
     p.tiles_cap = uint32_t(pairs / p.m_tile + groups + 1);
     // split K of the second product until about 8 wavefronts per CU have work
