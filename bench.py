@@ -51,6 +51,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cfg = inputs.CONFIGS[args.config]
+    if cfg.n_layers > 1:
+        return bench_streaming(cfg, args)
     t_setup = time.time()
     pool = harness.ExpertPool(cfg)
     w13, w2 = harness.make_layer_on_host(cfg, 0, 0, gen_device="cuda")
@@ -182,6 +184,103 @@ def main():
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(pool, cfg, blob, w13, w2, args.cpu_seconds)
+    print(json.dumps(result), flush=True)
+    pool.close()
+
+
+def bench_streaming(cfg, args):
+    """Config 5: all layers in order, 60 % of each layer's blocks in HBM, 40 % in pinned host
+    memory fetched on a side stream, two slot halves; steady-state time per layer."""
+    import numpy as np
+    import torch
+    from paper_2604_02715_amd import binding as B
+    from paper_2604_02715_amd import harness, inputs
+
+    t0 = time.time()
+    pool = harness.ExpertPool(cfg)
+    stats = []
+    for layer in range(cfg.n_layers):
+        w13, w2 = harness.make_layer_on_host(cfg, layer, 0, gen_device="cuda")
+        blob = pool.encode_layer(layer, w13, w2)
+        stats.append(pool.bind_layer(layer, blob, cfg.host_fraction, check=(layer == 0)))
+        del w13, w2, blob
+        print("layer %d encoded and bound: %d blocks, %d in pinned host (%.0f s)"
+              % (layer, stats[-1][0], stats[-1][1], time.time() - t0), file=sys.stderr, flush=True)
+    pool.bind_staging(2 * max(s[1] for s in stats) * 4096 + 8192)
+    routings = [inputs.routing(cfg, layer) for layer in range(cfg.n_layers)]
+    xs = [inputs.activations(cfg, layer).cuda() for layer in range(cfg.n_layers)]
+    outs = [torch.zeros((cfg.tokens, cfg.hidden), dtype=torch.float32, device="cuda") for _ in xs]
+    proxy = harness.StreamingProxy(pool, routings, xs, outs)
+    pool.reset_page_table()
+    setup_s = time.time() - t0
+
+    # parity on the fly: one overlapped pass, then the slots of the last two layers' last waves
+    # still hold their experts; compare them with regenerated originals
+    proxy.run_pass()
+    torch.cuda.synchronize()
+    assert pool.device_errors() == 0
+    if not args.no_check:
+        for layer in (cfg.n_layers - 2, cfg.n_layers - 1):
+            w13, w2 = inputs.layer_weights(cfg, layer, device="cuda")
+            w, slots = proxy.plan[layer][1][-1]
+            for e, s in zip(w, slots):
+                assert torch.equal(pool.slot13(int(s)), w13[int(e)].reshape(-1).view(torch.int16)), "decode mismatch"
+                assert torch.equal(pool.slot2(int(s)), w2[int(e)].reshape(-1).view(torch.int16)), "decode mismatch"
+            del w13, w2
+
+    def timed_passes(n_pass, **kw):
+        per_layer = []
+        for _ in range(n_pass):
+            evs = [torch.cuda.Event(enable_timing=True) for _ in range(cfg.n_layers)]
+            proxy.run_pass(layer_done_events=evs, **kw)
+            torch.cuda.synchronize()
+            per_layer.append([evs[i - 1].elapsed_time(evs[i]) for i in range(1, cfg.n_layers)])
+        return np.asarray(per_layer)
+
+    for _ in range(args.warmup if args.warmup < 3 else 1):
+        proxy.run_pass()
+    torch.cuda.synchronize()
+    n_pass = max(1, min(args.steps, 5))
+    t1 = time.perf_counter()
+    pl = timed_passes(n_pass)
+    wall = time.perf_counter() - t1
+    steady = pl[:, 1:]                                   # layers 2..N-1 of every pass
+    per_layer_ms = float(steady.mean())
+
+    # isolated components per layer (layer 2 as the sample): host fetch, decode, FFN
+    B.fluxmoe_profile_enable(pool.ctx, True)
+    B.fluxmoe_profile_collect(pool.ctx)
+    proxy.run_pass(single_stream=True)
+    torch.cuda.synchronize()
+    prof = B.fluxmoe_profile_collect(pool.ctx)
+    B.fluxmoe_profile_enable(pool.ctx, False)
+    decode_ms = prof["decode"][0] / cfg.n_layers
+    ffn_ms = sum(prof[k][0] for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")) / cfg.n_layers
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(proxy.copy_stream)
+    pool.prefetch_host(2, proxy.plan[2][0], proxy.copy_stream)
+    ev1.record(proxy.copy_stream)
+    torch.cuda.synchronize()
+    copy_ms = ev0.elapsed_time(ev1)
+    union = np.mean([len(u) for u, _ in proxy.plan])
+    host_bytes = float(np.mean([s[1] for s in stats])) * 4096 * union / cfg.n_experts
+    dense_bytes = union * (cfg.sigma1 + cfg.sigma2)
+    result = {
+        "metric": "streaming_steady_state_per_layer", "value": round(per_layer_ms, 3), "unit": "ms",
+        "n_gpus": 1, "steps": n_pass, "warmup": 1, "ms_per_step": round(wall / n_pass * 1e3, 2),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "layers": cfg.n_layers, "experts": cfg.n_experts, "hidden": cfg.hidden,
+                   "ffn": cfg.ffn, "tokens": cfg.tokens, "top_k": cfg.top_k, "slots": cfg.n_slots,
+                   "host_fraction": cfg.host_fraction, "mean_routed_union": round(float(union), 1),
+                   "waves_per_layer": round(float(np.mean([len(w) for _, w in proxy.plan])), 2)},
+        "per_layer": {"steady_ms_mean": round(per_layer_ms, 3), "steady_ms_std": round(float(steady.std()), 3),
+                      "host_fetch_ms_isolated": round(copy_ms, 3), "decode_ms_isolated": round(decode_ms, 3),
+                      "ffn_ms_isolated": round(ffn_ms, 3),
+                      "pcie_GBps": round(host_bytes / (copy_ms * 1e-3) / 1e9, 1),
+                      "overlap_efficiency": round(max(copy_ms, decode_ms + ffn_ms) / per_layer_ms, 3),
+                      "dense_out_GBps": round(dense_bytes / (per_layer_ms * 1e-3) / 1e9, 1)},
+        "setup_s": round(setup_s, 1),
+    }
     print(json.dumps(result), flush=True)
     pool.close()
 

@@ -161,9 +161,12 @@ int fluxmoe_reset_page_table(fluxmoe_ctx* ctx, int32_t* page_table, void* stream
  * Host-tier fetch (Sec. 4.2 "CPU offload backend": asynchronous DMA from pinned host
  * memory, overlapped with inference).  Enqueues on copy_stream the hipMemcpyAsync of every
  * host-tier block the listed experts of `layer` need into the staging half of that layer,
- * after waiting (on the device) for the last decode that read that half.  A following
- * fluxmoe_materialize of the same layer and experts waits for these copies.  Optional: if
- * it was not called, fluxmoe_materialize issues the copies on its own stream.
+ * after waiting (on the device) for the last decode that read that half.  Layer l uses half
+ * l & 1 and the half keeps the blocks until the next fetch into it, so one fetch can serve
+ * several fluxmoe_materialize calls (waves) of that layer over subsets of the listed experts;
+ * each of them waits for these copies.  Issue the fetch for layer l + 2 only after the last
+ * fluxmoe_materialize of layer l has been issued.  Optional: if the experts a materialize needs
+ * are not staged, it issues the copies on its own stream.
  */
 int fluxmoe_prefetch_host(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_ids,
                           uint32_t n, void* copy_stream);

@@ -45,9 +45,10 @@ namespace {
 constexpr int kRing = 4;
 constexpr uint32_t kLutBytes = kLutEntries * 4;
 
-struct StageState {
-    bool valid = false;
-    std::vector<int64_t> off[2];   // per expert: byte offset of the tensor's host part in the half
+// What one half of the host-tier staging buffer currently holds.
+struct StageHalf {
+    int64_t layer = -1;            // layer whose host-tier blocks are staged, -1 = nothing
+    std::vector<int64_t> off[2];   // per expert: byte offset of the tensor's host part, -1 = absent
 };
 
 struct FfnPlan {
@@ -89,9 +90,9 @@ struct fluxmoe_ctx {
     // host-tier staging
     uint8_t* staging = nullptr;
     size_t staging_bytes = 0;
-    std::vector<StageState> stage;
-    std::vector<hipEvent_t> ev_copied;
-    hipEvent_t ev_half_done[2] = {};
+    StageHalf half[2];                      // layer l stages into half l & 1
+    hipEvent_t ev_copied[2] = {};           // copies into the half have completed
+    hipEvent_t ev_half_done[2] = {};        // last decode that read the half
     bool half_done_valid[2] = {false, false};
     // launch shape of the decode kernel (FLUXMOE_DECODE_WAVES / FLUXMOE_DECODE_WG_PER_CU override)
     int tune_waves = 16;
@@ -185,16 +186,16 @@ int ensure_events(fluxmoe_ctx* c) {
     const uint32_t N = c->d.n_layers;
     c->ev_load.assign(N, nullptr);
     c->ev_infer.assign(N, nullptr);
-    c->ev_copied.assign(N, nullptr);
     for (uint32_t i = 0; i < N; ++i) {
         HIPCHECK(hipEventCreateWithFlags(&c->ev_load[i], hipEventDisableTiming));
         HIPCHECK(hipEventCreateWithFlags(&c->ev_infer[i], hipEventDisableTiming));
-        HIPCHECK(hipEventCreateWithFlags(&c->ev_copied[i], hipEventDisableTiming));
     }
     for (int i = 0; i < kRing; ++i)
         HIPCHECK(hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming));
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
         HIPCHECK(hipEventCreateWithFlags(&c->ev_half_done[i], hipEventDisableTiming));
+        HIPCHECK(hipEventCreateWithFlags(&c->ev_copied[i], hipEventDisableTiming));
+    }
     HIPCHECK(hipHostMalloc(reinterpret_cast<void**>(&c->pinned_cmd), size_t(kRing) * c->cmd_bytes,
                            hipHostMallocDefault));
     c->events_ready = true;
@@ -255,7 +256,6 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     c->slot_last_reader.assign(d.n_slots, -1);
     c->load_valid.assign(d.n_layers, 0);
     c->infer_valid.assign(d.n_layers, 0);
-    c->stage.resize(d.n_layers);
     compute_layout(c);
     if (const char* v = std::getenv("FLUXMOE_DECODE_WAVES")) {
         const int w = std::atoi(v);
@@ -279,9 +279,9 @@ int fluxmoe_destroy(fluxmoe_ctx* c) {
     if (c->events_ready) {
         for (auto e : c->ev_load) if (e) (void)hipEventDestroy(e);
         for (auto e : c->ev_infer) if (e) (void)hipEventDestroy(e);
-        for (auto e : c->ev_copied) if (e) (void)hipEventDestroy(e);
         for (int i = 0; i < kRing; ++i) if (c->ring_ev[i]) (void)hipEventDestroy(c->ring_ev[i]);
         for (int i = 0; i < 2; ++i) if (c->ev_half_done[i]) (void)hipEventDestroy(c->ev_half_done[i]);
+        for (int i = 0; i < 2; ++i) if (c->ev_copied[i]) (void)hipEventDestroy(c->ev_copied[i]);
         if (c->pinned_cmd) (void)hipHostFree(c->pinned_cmd);
     }
     delete c;
@@ -513,7 +513,7 @@ int fluxmoe_bind_layer(fluxmoe_ctx* c, uint32_t layer, const void* hbm_blocks, u
     L.host = static_cast<const uint8_t*>(host_blocks);
     L.n_host_blocks = n_host_blocks;
     L.bound = true;
-    c->stage[layer].valid = false;
+    if (c->half[layer & 1].layer == int64_t(layer)) c->half[layer & 1].layer = -1;
     return FLUXMOE_OK;
 }
 
@@ -523,7 +523,7 @@ int fluxmoe_bind_staging(fluxmoe_ctx* c, void* staging, size_t staging_bytes) {
     if (staging_bytes < 2ull * c->d.block_bytes) return set_error(FLUXMOE_ENOMEM, "staging too small");
     c->staging = static_cast<uint8_t*>(staging);
     c->staging_bytes = staging_bytes;
-    for (auto& s : c->stage) s.valid = false;
+    c->half[0].layer = c->half[1].layer = -1;
     return FLUXMOE_OK;
 }
 
@@ -548,20 +548,22 @@ static int validate_ids(const fluxmoe_ctx* c, const int32_t* ids, uint32_t n) {
     return FLUXMOE_OK;
 }
 
-// Copies of the listed experts' host-tier blocks into the layer's staging half.
+// Copies of the listed experts' host-tier blocks into the layer's staging half (layer & 1).
+// The half keeps them until the next staging into it; the copies wait (on the device) for the
+// last decode that read the half.
 static int stage_host_blocks(fluxmoe_ctx* c, uint32_t layer, const int32_t* ids, uint32_t n,
                              hipStream_t s) {
     LayerMeta& L = c->layers[layer];
-    StageState& st = c->stage[layer];
-    st.valid = false;
+    const int h = layer & 1;
+    StageHalf& st = c->half[h];
+    st.layer = -1;
     st.off[0].assign(c->d.n_experts, -1);
     st.off[1].assign(c->d.n_experts, -1);
-    if (L.n_host_blocks == 0) { st.valid = true; return FLUXMOE_OK; }
+    if (L.n_host_blocks == 0) { st.layer = layer; return FLUXMOE_OK; }
     if (!c->staging) return set_error(FLUXMOE_ESTATE, "layer %u has host-tier blocks but no staging buffer is bound", layer);
     const uint32_t B = c->d.block_bytes;
-    const int half = layer & 1;
     const uint64_t half_bytes = (c->staging_bytes / 2) / B * B;
-    uint8_t* base = c->staging + half * half_bytes;
+    uint8_t* base = c->staging + h * half_bytes;
     std::vector<int32_t> sorted(ids, ids + n);
     std::sort(sorted.begin(), sorted.end());
     struct Range { uint64_t a, b, dst; };
@@ -580,11 +582,11 @@ static int stage_host_blocks(fluxmoe_ctx* c, uint32_t layer, const int32_t* ids,
     if (cursor > half_bytes)
         return set_error(FLUXMOE_ENOMEM, "staging half holds %llu bytes, layer %u needs %llu",
                          (unsigned long long)half_bytes, layer, (unsigned long long)cursor);
-    if (c->half_done_valid[half]) HIPCHECK(hipStreamWaitEvent(s, c->ev_half_done[half], 0));
+    if (c->half_done_valid[h]) HIPCHECK(hipStreamWaitEvent(s, c->ev_half_done[h], 0));
     for (const Range& r : ranges)
         HIPCHECK(hipMemcpyAsync(base + r.dst, L.host + r.a * B, (r.b - r.a) * B, hipMemcpyHostToDevice, s));
-    HIPCHECK(hipEventRecord(c->ev_copied[layer], s));
-    st.valid = true;
+    HIPCHECK(hipEventRecord(c->ev_copied[h], s));
+    st.layer = layer;
     return FLUXMOE_OK;
 }
 
@@ -623,8 +625,8 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
             if (L.tensors[ti][expert_ids[i]].first_block < L.n_host_blocks) need_host = true;
     bool wait_copy = false;
     if (need_host) {
-        StageState& st = c->stage[layer];
-        bool staged = st.valid;
+        StageHalf& st = c->half[layer & 1];
+        bool staged = st.layer == int64_t(layer);
         for (uint32_t i = 0; i < n && staged; ++i)
             for (int ti = 0; ti < 2; ++ti)
                 if (L.tensors[ti][expert_ids[i]].first_block < L.n_host_blocks && st.off[ti][expert_ids[i]] < 0)
@@ -660,7 +662,7 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
             const uint64_t hb = std::min(b, std::max(a, L.n_host_blocks));   // host part is [a, hb)
             const uint64_t dst = uint64_t(uintptr_t(arena)) + uint64_t(dst_slots[i]) * sigma;
             if (hb > a) {
-                const uint8_t* src = c->staging + half * half_bytes + c->stage[layer].off[ti][expert_ids[i]];
+                const uint8_t* src = c->staging + half * half_bytes + c->half[half].off[ti][expert_ids[i]];
                 jobs[nj++] = DecodeJob{uint64_t(uintptr_t(src)), dst, blocks, uint32_t(hb - a),
                                        uint32_t(ti == 0 ? c->elems13 : c->elems2), 0};
                 blocks += uint32_t(hb - a);
@@ -709,7 +711,7 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
 
     // enqueue: WAR waits, host-tier copies, command upload, decode, events
     for (int32_t lr : wait_layers) HIPCHECK(hipStreamWaitEvent(stream, c->ev_infer[lr], 0));
-    if (wait_copy) HIPCHECK(hipStreamWaitEvent(stream, c->ev_copied[layer], 0));
+    if (wait_copy) HIPCHECK(hipStreamWaitEvent(stream, c->ev_copied[half], 0));
     const size_t used = upd_off + touched.size() * 8;
     HIPCHECK(hipMemcpyAsync(dcmd, hcmd, used, hipMemcpyHostToDevice, stream));
 
@@ -739,7 +741,6 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
     if (need_host) {
         HIPCHECK(hipEventRecord(c->ev_half_done[half], stream));
         c->half_done_valid[half] = true;
-        c->stage[layer].valid = false;
     }
     HIPCHECK(hipEventRecord(c->ev_load[layer], stream));
     c->load_valid[layer] = 1;

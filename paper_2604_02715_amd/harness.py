@@ -133,3 +133,66 @@ def make_layer_on_host(cfg: inputs.LayerConfig, layer=0, seed=0, gen_device="cpu
     """Synthetic layer weights as CPU BF16 tensors (generated on gen_device, copied back)."""
     w13, w2 = inputs.layer_weights(cfg, layer, device=gen_device, seed=seed)
     return w13.cpu().contiguous(), w2.cpu().contiguous()
+
+
+class StreamingProxy:
+    """The forward proxy of Sec. 3 over all layers of a pool, with Alg. 1's stream layout.
+
+    Layer l materializes into the slot half l & 1 (two reusable halves, Sec. 4.1) on the load
+    stream while layer l - 1 runs its FFN on the inference stream; host-tier blocks of layer
+    l + 2 are fetched on the copy stream as soon as layer l's last materialize has been issued.
+    A routed union larger than one half is cut into waves (materialize, FFN with
+    skip-unmapped/accumulate, release).  Ordering between the streams is entirely the
+    library's (events inside fluxmoe_materialize / fluxmoe_expert_ffn / fluxmoe_prefetch_host).
+    """
+
+    def __init__(self, pool: ExpertPool, routings, xs, outs, seed=0):
+        cfg = pool.cfg
+        self.pool, self.cfg = pool, cfg
+        self.xs, self.outs = xs, outs
+        self.ids = [torch.from_numpy(r[0]).to(pool.device) for r in routings]
+        self.gates = [torch.from_numpy(r[1]).to(pool.device) for r in routings]
+        self.half = cfg.n_slots // 2
+        self.plan = []                      # per layer: list of (expert ids, slots)
+        for layer, (ids_np, _) in enumerate(routings):
+            union = sorted(int(e) for e in inputs.routed_union(ids_np))
+            base = (layer & 1) * self.half
+            waves = []
+            for w0 in range(0, len(union), self.half):
+                w = union[w0:w0 + self.half]
+                perm = inputs.slot_permutation(self.half, cfg.name, seed, layer, w0)[:len(w)]
+                waves.append((np.asarray(w, dtype=np.int32), (base + perm).astype(np.int32)))
+            self.plan.append((np.asarray(union, dtype=np.int32), waves))
+        self.load_stream = torch.cuda.Stream()
+        self.infer_stream = torch.cuda.Stream()
+        self.copy_stream = torch.cuda.Stream()
+
+    def run_pass(self, layer_done_events=None, single_stream=False, ffn_delay_cycles=0):
+        """Issue one pass over all layers.  single_stream=True puts everything on the
+        inference stream in program order (the reference schedule for hazard checks).
+        ffn_delay_cycles > 0 holds the inference stream back before every FFN (a bounded
+        spin kernel), which widens the window in which a missing write-after-read wait would
+        let the next materialize overwrite slots that the FFN has not read yet."""
+        p, n_layers = self.pool, self.cfg.n_layers
+        ls = self.infer_stream if single_stream else self.load_stream
+        cs = self.infer_stream if single_stream else self.copy_stream
+        host = self.cfg.host_fraction > 0
+        if host:
+            p.prefetch_host(0, self.plan[0][0], cs)
+            if n_layers > 1:
+                p.prefetch_host(1, self.plan[1][0], cs)
+        for layer in range(n_layers):
+            union, waves = self.plan[layer]
+            for wi, (w, slots) in enumerate(waves):
+                p.materialize(layer, w, slots, ls)
+                if host and wi == len(waves) - 1 and layer + 2 < n_layers:
+                    p.prefetch_host(layer + 2, self.plan[layer + 2][0], cs)
+                flags = (B.FFN_SKIP_UNMAPPED if len(waves) > 1 else 0) | (B.FFN_ACCUMULATE if wi else 0)
+                if ffn_delay_cycles:
+                    with torch.cuda.stream(self.infer_stream):
+                        torch.cuda._sleep(int(ffn_delay_cycles))
+                p.expert_ffn(layer, self.xs[layer], self.ids[layer], self.gates[layer], self.outs[layer],
+                             flags, self.infer_stream)
+                p.release(layer, w, self.infer_stream)
+            if layer_done_events is not None:
+                layer_done_events[layer].record(self.infer_stream)
