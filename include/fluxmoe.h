@@ -240,6 +240,20 @@ int fluxmoe_profile_enable(fluxmoe_ctx* ctx, int on);
 int fluxmoe_profile_collect(fluxmoe_ctx* ctx, double out_ms[FLUXMOE_PROFILE_KINDS],
                             uint32_t out_count[FLUXMOE_PROFILE_KINDS]);
 
+/*
+ * The shared expert of a layer (Sec. 3 excludes shared experts from the routed set; Sec. 4.2
+ * keeps their weights uncompressed and GPU resident): the same SwiGLU FFN applied to every
+ * token with gate 1, on dense weights the caller keeps resident.
+ *   w13 device BF16 [2][hidden][ffn], w2 device BF16 [ffn][hidden], 16-byte aligned
+ *   tokens device BF16 [T][hidden]; out device float [T][hidden]
+ *   flags: 0 or FLUXMOE_FFN_ACCUMULATE (out += result, e.g. after fluxmoe_expert_ffn)
+ * Uses the bound workspace (fluxmoe_ffn_workspace_bytes with shared_expert != 0) and the
+ * stream's order only; it takes no part in the slot event protocol.
+ */
+int fluxmoe_shared_expert_ffn(fluxmoe_ctx* ctx, const uint16_t* w13, const uint16_t* w2,
+                              const uint16_t* tokens, uint32_t T, float* out, uint32_t flags,
+                              void* stream);
+
 /* Synchronous: read and clear the device error word (0 = none; bit 0 a block failed
  * validation during decode and was skipped, bit 1 an unmapped expert was routed to). */
 int fluxmoe_device_errors(fluxmoe_ctx* ctx, uint32_t* out_flags);

@@ -68,6 +68,8 @@ EXPORTS = {
     "fluxmoe_expert_ffn": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
                                      C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
                                      C.c_void_p]),
+    "fluxmoe_shared_expert_ffn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                            C.c_void_p, C.c_uint32, C.c_void_p]),
     "fluxmoe_stream_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]),
     "fluxmoe_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "fluxmoe_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]),
@@ -195,6 +197,10 @@ def fluxmoe_expert_ffn(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K, p
                        out_ptr, flags=0, stream=None):
     _check(lib().fluxmoe_expert_ffn(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K,
                                     page_table_ptr, out_ptr, flags, stream))
+
+
+def fluxmoe_shared_expert_ffn(ctx, w13_ptr, w2_ptr, tokens_ptr, T, out_ptr, flags=0, stream=None):
+    _check(lib().fluxmoe_shared_expert_ffn(ctx, w13_ptr, w2_ptr, tokens_ptr, T, out_ptr, flags, stream))
 
 
 def fluxmoe_stream_copy(dst_ptr, src_ptr, nbytes, n_workgroups, stream=None):

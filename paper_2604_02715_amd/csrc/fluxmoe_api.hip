@@ -307,10 +307,18 @@ int fluxmoe_query_sizes(const fluxmoe_ctx* c, fluxmoe_sizes* out) {
     return FLUXMOE_OK;
 }
 
+// extra scratch of the shared-expert call: its synthetic routing (ids, gates, one-entry table)
+static uint64_t shared_extra_bytes(uint32_t T) { return 2 * align_up(uint64_t(T) * 4, 256) + 256; }
+
 uint64_t fluxmoe_ffn_workspace_bytes(const fluxmoe_ctx* c, uint32_t T, uint32_t K, int shared_expert) {
     if (!c) return 0;
-    (void)shared_expert;
-    return plan_ffn(c, T, K).bytes;
+    uint64_t need = plan_ffn(c, T, K).bytes;
+    if (shared_expert) {
+        fluxmoe_ctx one = *c;          // same shapes, a single expert
+        one.d.n_experts = 1;
+        need = std::max(need, plan_ffn(&one, T, 1).bytes + shared_extra_bytes(T));
+    }
+    return need;
 }
 
 int fluxmoe_encode_pool(fluxmoe_ctx* c, uint32_t layer, const uint16_t* w13, const uint16_t* w2,
@@ -832,6 +840,59 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, u
     const int64_t lo = int64_t(layer) * c->d.n_experts, hi = lo + c->d.n_experts;
     for (uint32_t s = 0; s < c->d.n_slots; ++s)
         if (c->slot_owner[s] >= lo && c->slot_owner[s] < hi) c->slot_last_reader[s] = int32_t(layer);
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_shared_expert_ffn(fluxmoe_ctx* c, const uint16_t* w13, const uint16_t* w2,
+                              const uint16_t* tokens, uint32_t T, float* out, uint32_t flags,
+                              void* stream_v) {
+    if (!c) return set_error(FLUXMOE_EINVAL, "ctx is NULL");
+    if (!c->arenas_bound) return set_error(FLUXMOE_ESTATE, "fluxmoe_bind_arenas has not been called");
+    if (T == 0) return FLUXMOE_OK;
+    if (!w13 || !w2 || !tokens || !out) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    if (flags & ~1u) return set_error(FLUXMOE_EINVAL, "only FLUXMOE_FFN_ACCUMULATE is accepted");
+    if (T > 65535) return set_error(FLUXMOE_EINVAL, "T too large");
+    if ((uintptr_t(w13) | uintptr_t(w2) | uintptr_t(tokens) | uintptr_t(out)) & 15)
+        return set_error(FLUXMOE_EINVAL, "pointers must be 16-byte aligned");
+    fluxmoe_ctx one = *c;              // shapes of this model with a single, always-mapped expert
+    one.d.n_experts = 1;
+    const FfnPlan p = plan_ffn(&one, T, 1);
+    const uint64_t extra = shared_extra_bytes(T);
+    if (c->pool_ws_bytes + p.bytes + extra > c->ws_bytes)
+        return set_error(FLUXMOE_ENOMEM, "workspace has %zu bytes, the shared expert with T=%u needs %llu",
+                         c->ws_bytes, T, (unsigned long long)(c->pool_ws_bytes + p.bytes + extra));
+    if (p.tiles_cap > 65535) return set_error(FLUXMOE_EINVAL, "too many row tiles (%u)", p.tiles_cap);
+    hipStream_t stream = static_cast<hipStream_t>(stream_v);
+    uint8_t* w = c->ws + c->pool_ws_bytes;
+    uint8_t* x = w + p.bytes;
+    int32_t* ids = reinterpret_cast<int32_t*>(x);
+    int32_t* gates = reinterpret_cast<int32_t*>(x + align_up(uint64_t(T) * 4, 256));
+    int32_t* table = reinterpret_cast<int32_t*>(x + 2 * align_up(uint64_t(T) * 4, 256));
+    HIPCHECK(launch_fill_i32(ids, 0, T, stream));
+    HIPCHECK(launch_fill_i32(gates, 0x3F800000, T, stream));      // 1.0f
+    HIPCHECK(launch_fill_i32(table, 0, 1, stream));
+    FfnArgs a{};
+    a.tokens = tokens;
+    a.topk_ids = ids;
+    a.topk_w = reinterpret_cast<const float*>(gates);
+    a.page_table = table;
+    a.slots13 = w13;
+    a.slots2 = w2;
+    a.out = out;
+    a.T = T; a.K = 1; a.H = c->d.hidden; a.F = c->d.ffn; a.E = 1;
+    a.flags = flags;
+    a.expert_count = reinterpret_cast<int32_t*>(w + p.off_count);
+    a.expert_offset = reinterpret_cast<int32_t*>(w + p.off_offset);
+    a.sorted_pair = reinterpret_cast<int32_t*>(w + p.off_sorted);
+    a.pair_pos = reinterpret_cast<int32_t*>(w + p.off_pos);
+    a.tile_expert = reinterpret_cast<int32_t*>(w + p.off_tile_e);
+    a.tile_row0 = reinterpret_cast<int32_t*>(w + p.off_tile_r);
+    a.n_tiles = reinterpret_cast<int32_t*>(w + p.off_ntiles);
+    a.hbuf = reinterpret_cast<uint16_t*>(w + p.off_h);
+    a.ybuf = reinterpret_cast<float*>(w + p.off_y);
+    a.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
+    a.pairs_cap = p.pairs_cap; a.tiles_cap = p.tiles_cap; a.m_tile = p.m_tile; a.ksplit = p.ksplit;
+    HIPCHECK(launch_ffn(a, c->n_cus, stream, c->profiling ? ffn_span_hook : nullptr, c));
     return FLUXMOE_OK;
 }
 

@@ -25,7 +25,7 @@ class ExpertPool:
         self.sizes = B.fluxmoe_query_sizes(self.ctx)
         T = max_tokens or cfg.tokens
         K = max_top_k or cfg.top_k
-        ffn_ws = B.fluxmoe_ffn_workspace_bytes(self.ctx, T, K)
+        ffn_ws = B.fluxmoe_ffn_workspace_bytes(self.ctx, T, K, cfg.shared_expert)
         self.ws_bytes = int(self.sizes.pool_workspace_bytes + ffn_ws)
         dev = self.device
         self.slots13 = torch.empty(self.sizes.slots13_bytes // 2, dtype=torch.int16, device=dev)
@@ -107,6 +107,11 @@ class ExpertPool:
         B.fluxmoe_expert_ffn(self.ctx, layer, tokens.data_ptr(), T, topk_ids.data_ptr(),
                              topk_w.data_ptr(), K, self.page_table.data_ptr(), out.data_ptr(), flags,
                              _sptr(stream))
+
+    def shared_expert_ffn(self, w13, w2, tokens, out, flags=0, stream=None):
+        assert w13.dtype == torch.bfloat16 and w13.is_contiguous() and w2.is_contiguous()
+        B.fluxmoe_shared_expert_ffn(self.ctx, w13.data_ptr(), w2.data_ptr(), tokens.data_ptr(),
+                                    tokens.shape[0], out.data_ptr(), flags, _sptr(stream))
 
     def device_errors(self):
         return B.fluxmoe_device_errors(self.ctx)

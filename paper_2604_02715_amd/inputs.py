@@ -111,6 +111,11 @@ def expert_weights(cfg: LayerConfig, layer: int, expert: int, device="cpu", seed
     return torch.stack([w1, w3], dim=0), w2
 
 
+def shared_expert_weights(cfg: LayerConfig, layer: int, device="cpu", seed: int = 0):
+    """Dense (never compressed) weights of the layer's shared expert, same shapes and recipe."""
+    return expert_weights(cfg, layer, 1_000_000, device, seed)
+
+
 def layer_weights(cfg: LayerConfig, layer: int, device="cpu", seed: int = 0,
                   out13: torch.Tensor | None = None, out2: torch.Tensor | None = None):
     """All routed experts of one layer: w13 [E][2][H][F], w2 [E][F][H] (BF16)."""

@@ -104,3 +104,35 @@ def test_unmapped_expert_without_skip_flag_sets_the_error_word():
         assert pool.device_errors() == 2
     finally:
         pool.close()
+
+
+def test_shared_expert_added_on_top_of_the_routed_experts():
+    """Configs 3 and 4 carry one shared expert: dense resident weights, every token, gate 1."""
+    from gpu_common import build_pool
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], shared_expert=True, tokens=70, hidden=136, ffn=264)
+    pool, dense = build_pool(cfg)
+    try:
+        w13, w2 = dense[0]
+        s13, s2 = inputs.shared_expert_weights(cfg, 0)
+        x = inputs.activations(cfg)
+        ids, g = inputs.routing(cfg)
+        out = torch.zeros((cfg.tokens, cfg.hidden), dtype=torch.float32, device="cuda")
+        xd = x.cuda()
+        s13d, s2d = s13.cuda(), s2.cuda()
+        pool.reset_page_table()
+        pool.materialize(0, np.arange(cfg.n_experts), np.arange(cfg.n_experts))
+        pool.expert_ffn(0, xd, torch.from_numpy(ids).cuda(), torch.from_numpy(g).cuda(), out)
+        pool.shared_expert_ffn(s13d, s2d, xd, out, B.FFN_ACCUMULATE)
+        alone = torch.full_like(out, 5.0)
+        pool.shared_expert_ffn(s13d, s2d, xd, alone)
+        torch.cuda.synchronize()
+        assert pool.device_errors() == 0
+        xb = inputs.bits_u16(x)
+        routed = offn.moe_ffn(xb, ids, g, lambda e: (inputs.bits_u16(w13[e]), inputs.bits_u16(w2[e])))
+        T = cfg.tokens
+        shared = offn.moe_ffn(xb, np.zeros((T, 1), dtype=np.int32), np.ones((T, 1), dtype=np.float32),
+                              lambda e: (inputs.bits_u16(s13), inputs.bits_u16(s2)))
+        assert offn.rel_frobenius(alone.cpu().numpy(), shared) <= TOL
+        assert offn.rel_frobenius(out.cpu().numpy(), routed + shared) <= TOL
+    finally:
+        pool.close()

@@ -86,12 +86,21 @@ def run_full(cfg, n_sample_tokens=3):
             if len(waves) > 1:
                 model.release(0, w)
                 pool.release(0, w)
+        if cfg.shared_expert:                      # dense resident weights, all tokens, gate 1
+            s13, s2 = inputs.shared_expert_weights(cfg, 0, device="cuda")
+            pool.shared_expert_ffn(s13, s2, xd, out, B.FFN_ACCUMULATE)
         torch.cuda.synchronize()
+        assert pool.device_errors() == 0
         # FFN on sampled tokens
         rng = np.random.default_rng(5)
         sel = np.sort(rng.choice(cfg.tokens, n_sample_tokens, replace=False))
         weights = lambda e: (inputs.bits_u16(w13[e]), inputs.bits_u16(w2[e]))
         want = offn.moe_ffn(inputs.bits_u16(x)[sel], ids[sel], g[sel], weights, round_h=True)
+        if cfg.shared_expert:
+            s13h, s2h = inputs.bits_u16(s13.cpu()), inputs.bits_u16(s2.cpu())
+            n = len(sel)
+            want = want + offn.moe_ffn(inputs.bits_u16(x)[sel], np.zeros((n, 1), dtype=np.int32),
+                                       np.ones((n, 1), dtype=np.float32), lambda e: (s13h, s2h), round_h=True)
         got = out[torch.from_numpy(sel).cuda()].cpu().numpy()
         err = offn.rel_frobenius(got, want)
         print(cfg.name, "FFN rel. Frobenius error on tokens", sel.tolist(), "= %.3e" % err, flush=True)

@@ -1,0 +1,143 @@
+"""CPU-only checks of libfluxmoe.so: it loads without a GPU, exports every symbol the header
+declares, and its host logic (offline encoder, metadata, argument validation) agrees with the
+oracle.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import codec
+from paper_2604_02715_amd import binding as B
+from paper_2604_02715_amd import inputs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "fluxmoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fluxmoe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol_and_binding_covers_them():
+    names = header_functions()
+    assert "fluxmoe_encode_pool" in names and "fluxmoe_materialize" in names and "fluxmoe_expert_ffn" in names
+    lib = B.lib()
+    for n in names:
+        assert hasattr(lib, n), "libfluxmoe.so does not export " + n
+        assert n in B.EXPORTS, "binding.py has no prototype for " + n
+    assert sorted(B.EXPORTS) == names
+
+
+def make(cfg):
+    ctx = B.fluxmoe_create(cfg.n_layers, cfg.n_experts, cfg.hidden, cfg.ffn, cfg.n_slots)
+    w13, w2 = inputs.layer_weights(cfg, 0)
+    w13, w2 = inputs.bits_u16(w13), inputs.bits_u16(w2)
+    cap = B.fluxmoe_query_sizes(ctx).layer_blob_bound
+    dst = np.zeros(cap, dtype=np.uint8)
+    return ctx, w13, w2, dst
+
+
+def test_encoder_matches_the_oracle_and_is_thread_count_independent():
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=5, hidden=128, ffn=192)
+    ctx, w13, w2, dst = make(cfg)
+    used = B.fluxmoe_encode_pool(ctx, 0, w13.ctypes.data, w2.ctypes.data, dst.ctypes.data, dst.size, 1)
+    blob1 = dst[:used].copy()
+    dst[:] = 0xAA
+    used8 = B.fluxmoe_encode_pool(ctx, 0, w13.ctypes.data, w2.ctypes.data, dst.ctypes.data, dst.size, 8)
+    assert used8 == used and np.array_equal(dst[:used], blob1)
+    info = B.fluxmoe_layer_info_get(ctx, 0)
+    assert info.n_blocks * 4096 == used
+    assert list(info.elements) == [5 * 2 * 128 * 192, 5 * 128 * 192]
+    # total payload bits = the unique optimum: equal to the oracle's lengths' cost
+    for ti, (d, arr) in enumerate(((1, w13), (2, w2))):
+        hist = codec.exponent_histogram(arr)
+        lens_o = codec.code_lengths(hist, 12)
+        lens_l = B.fluxmoe_code_lengths(ctx, 0, d)
+        assert codec.payload_bits(hist, lens_l) == codec.payload_bits(hist, lens_o) == info.payload_bits[ti]
+        assert abs(sum(2.0 ** -int(l) for l in lens_l[lens_l > 0]) - 1.0) < 1e-12
+    # the oracle decodes every tensor of the library's pool back to the original bits
+    blocks = blob1.reshape(-1, 4096)
+    seen = 0
+    for d, arr in ((2, w2), (1, w13)):
+        lens = B.fluxmoe_code_lengths(ctx, 0, d)
+        for e in range(5):
+            b0, nb = B.fluxmoe_tensor_blocks(ctx, 0, d, e)
+            assert b0 == seen                       # blob order: type 2 first, experts ascending
+            seen += nb
+            first = B.fluxmoe_tensor_first_elems(ctx, 0, d, e)
+            assert first[0] == 0 and first[-1] == arr[e].size and (np.diff(first.astype(np.int64)) > 0).all()
+            assert np.array_equal(codec.decode_tensor(blocks[b0:b0 + nb], lens, arr[e].size), arr[e].reshape(-1))
+    assert seen == info.n_blocks
+    B.fluxmoe_destroy(ctx)
+
+
+def test_encoder_on_adversarial_tensors_round_trips_through_the_oracle():
+    adv = inputs.adversarial_tensors()
+    names = sorted(adv)
+    H, F, E = 64, 128, len(names)
+    ctx = B.fluxmoe_create(1, E, H, F, 2, max_code_len=12)
+    w2 = np.stack([np.resize(adv[n], H * F) for n in names])
+    w13 = np.stack([np.resize(adv[n][::-1], 2 * H * F) for n in names])
+    dst = np.zeros(B.fluxmoe_query_sizes(ctx).layer_blob_bound, dtype=np.uint8)
+    used = B.fluxmoe_encode_pool(ctx, 0, w13.ctypes.data, w2.ctypes.data, dst.ctypes.data, dst.size, 4)
+    blocks = dst[:used].reshape(-1, 4096)
+    for d, arr in ((1, w13), (2, w2)):
+        lens = B.fluxmoe_code_lengths(ctx, 0, d)
+        assert lens.max() <= 12
+        for e in range(E):
+            b0, nb = B.fluxmoe_tensor_blocks(ctx, 0, d, e)
+            assert np.array_equal(codec.decode_tensor(blocks[b0:b0 + nb], lens, arr[e].size), arr[e])
+    B.fluxmoe_destroy(ctx)
+
+
+def test_length_limit_parameter():
+    H, F = 64, 64
+    rng = np.random.default_rng(0)
+    geo = np.minimum(rng.geometric(0.5, 2 * H * F), 40).astype(np.uint16)
+    w13 = ((100 + geo) << 7).astype(np.uint16).reshape(1, 2, H, F)
+    w2 = w13[0, 0].reshape(1, F, H).copy()
+    for lmax in (8, 10, 12):
+        ctx = B.fluxmoe_create(1, 1, H, F, 1, max_code_len=lmax)
+        dst = np.zeros(B.fluxmoe_query_sizes(ctx).layer_blob_bound, dtype=np.uint8)
+        B.fluxmoe_encode_pool(ctx, 0, w13.ctypes.data, w2.ctypes.data, dst.ctypes.data, dst.size, 2)
+        lens = B.fluxmoe_code_lengths(ctx, 0, 1)
+        hist = codec.exponent_histogram(w13)
+        assert lens.max() == lmax
+        assert codec.payload_bits(hist, lens) == codec.payload_bits(hist, codec.code_lengths(hist, lmax))
+        B.fluxmoe_destroy(ctx)
+
+
+def test_argument_validation_on_the_host():
+    for kw, status in ((dict(hidden=100), -1), (dict(block_bytes=8192), -1), (dict(max_code_len=13), -1),
+                       (dict(n_slots=0), -1), (dict(n_experts=5000), -1)):
+        args = dict(n_layers=1, n_experts=4, hidden=64, ffn=64, n_slots=2)
+        args.update(kw)
+        with pytest.raises(B.FluxmoeError) as ei:
+            B.fluxmoe_create(**args)
+        assert ei.value.status == status
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=2, hidden=64, ffn=64)
+    ctx, w13, w2, dst = make(cfg)
+    with pytest.raises(B.FluxmoeError) as ei:                       # destination too small
+        B.fluxmoe_encode_pool(ctx, 0, w13.ctypes.data, w2.ctypes.data, dst.ctypes.data, 4096, 2)
+    assert ei.value.status == -2 and "needs" in str(ei.value)
+    with pytest.raises(B.FluxmoeError) as ei:                       # layer out of range
+        B.fluxmoe_encode_pool(ctx, 3, w13.ctypes.data, w2.ctypes.data, dst.ctypes.data, dst.size, 2)
+    assert ei.value.status == -4
+    with pytest.raises(B.FluxmoeError) as ei:                       # metadata of a layer never encoded
+        B.fluxmoe_layer_info_get(ctx, 0)
+    assert ei.value.status == -6
+    B.fluxmoe_encode_pool(ctx, 0, w13.ctypes.data, w2.ctypes.data, dst.ctypes.data, dst.size, 2)
+    with pytest.raises(B.FluxmoeError) as ei:
+        B.fluxmoe_tensor_blocks(ctx, 0, 3, 0)
+    assert ei.value.status == -1
+    with pytest.raises(B.FluxmoeError) as ei:
+        B.fluxmoe_tensor_blocks(ctx, 0, 1, 2)
+    assert ei.value.status == -4
+    with pytest.raises(B.FluxmoeError) as ei:                       # nothing is bound yet
+        B.fluxmoe_materialize(ctx, 0, [0], 1 << 20, [0])
+    assert ei.value.status == -6
+    assert B.fluxmoe_ffn_workspace_bytes(ctx, 64, 2) > 0
+    B.fluxmoe_destroy(ctx)
