@@ -36,6 +36,9 @@ def main():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--ffn-rows-per-expert", type=int, default=0,
+                    help="FFN-only sweep point: balanced routing with this many rows per expert "
+                         "(prefill-shaped batch) on the config's layer shape; reports TFLOP/s")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic) and report their rate; "
                          "under rocprofv3 --pmc they calibrate FETCH_SIZE / WRITE_SIZE")
@@ -53,6 +56,8 @@ def main():
     cfg = inputs.CONFIGS[args.config]
     if cfg.n_layers > 1:
         return bench_streaming(cfg, args)
+    if args.ffn_rows_per_expert:
+        return bench_ffn_rows(cfg, args)
     t_setup = time.time()
     pool = harness.ExpertPool(cfg)
     w13, w2 = harness.make_layer_on_host(cfg, 0, 0, gen_device="cuda")
@@ -185,6 +190,71 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(pool, cfg, blob, w13, w2, args.cpu_seconds)
     print(json.dumps(result), flush=True)
+    pool.close()
+
+
+def bench_ffn_rows(cfg, args):
+    """FFN only, M rows per expert on every expert of the layer (balanced synthetic routing):
+    the MFMA-bound side of the expert GEMM.  Materialization runs once, untimed."""
+    import numpy as np
+    import torch
+    from paper_2604_02715_amd import binding as B
+    from paper_2604_02715_amd import harness, inputs
+
+    M, E, K = args.ffn_rows_per_expert, cfg.n_experts, cfg.top_k
+    T = M * E // K
+    big = inputs.scaled(cfg, tokens=T)
+    pool = harness.ExpertPool(big)
+    w13, w2 = harness.make_layer_on_host(cfg, 0, 0, gen_device="cuda")
+    pool.bind_layer(0, pool.encode_layer(0, w13, w2))
+    pool.reset_page_table()
+    pool.materialize(0, np.arange(E), np.arange(E))
+    t = np.arange(T)
+    ids_np = np.stack([(t + j * (E // K)) % E for j in range(K)], axis=1).astype(np.int32)
+    assert (np.bincount(ids_np.reshape(-1), minlength=E) == M).all()
+    g_np = np.full((T, K), 1.0 / K, dtype=np.float32)
+    x = inputs.activations(big).cuda()
+    ids, g = torch.from_numpy(ids_np).cuda(), torch.from_numpy(g_np).cuda()
+    out = torch.zeros((T, cfg.hidden), dtype=torch.float32, device="cuda")
+    for _ in range(max(1, args.warmup)):
+        pool.expert_ffn(0, x, ids, g, out)
+    torch.cuda.synchronize()
+    B.fluxmoe_profile_enable(pool.ctx, True)
+    B.fluxmoe_profile_collect(pool.ctx)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        pool.expert_ffn(0, x, ids, g, out)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    prof = B.fluxmoe_profile_collect(pool.ctx)
+    assert pool.device_errors() == 0
+    flops = 6.0 * cfg.hidden * cfg.ffn * T * K
+    g1 = prof["gemm1_swiglu"][0] / args.steps
+    g2 = prof["gemm2"][0] / args.steps
+    # spot check against the oracle on two tokens
+    if not args.no_check:
+        from oracle import ffn as offn
+        sel = np.array([0, T - 1])
+        want = offn.moe_ffn(inputs.bits_u16(x.cpu())[sel], ids_np[sel], g_np[sel],
+                            lambda e: (inputs.bits_u16(w13[e]), inputs.bits_u16(w2[e])), round_h=True)
+        err = offn.rel_frobenius(out[torch.from_numpy(sel).cuda()].cpu().numpy(), want)
+        assert err <= 1e-3, err
+    tf = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "expert_ffn_throughput", "value": round(tf, 1), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name + "_ffn_rows", "rows_per_expert": M, "experts": E, "hidden": cfg.hidden,
+                   "ffn": cfg.ffn, "tokens": T, "top_k": K},
+        "roofline": {"kernel": "gemm1_swiglu", "bound": "mfma",
+                     "achieved": round(4.0 * cfg.hidden * cfg.ffn * T * K / (g1 * 1e-3) / 1e12, 1),
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(4.0 * cfg.hidden * cfg.ffn * T * K / (g1 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": None, "avg_launch_ms": round(g1, 4)},
+        "ffn": {"frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                "gemm2_TFLOPs": round(2.0 * cfg.hidden * cfg.ffn * T * K / (g2 * 1e-3) / 1e12, 1),
+                "kernels_ms": {k: round(prof[k][0] / max(1, prof[k][1]), 4)
+                               for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")}}}), flush=True)
     pool.close()
 
 

@@ -125,9 +125,11 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
     const uint64_t groups = std::max<uint64_t>(1, std::min<uint64_t>(E, pairs));
     const uint64_t avg = (pairs + groups - 1) / groups;
     p.m_tile = avg > 32 ? 64 : (avg > 16 ? 32 : 16);
+    // many rows per expert: the LDS-tiled MFMA kernels (they need k extents that are multiples of 64)
+    if (avg >= 192 && H % 64 == 0 && F % 64 == 0) p.m_tile = 256;
     if (const char* v = std::getenv("FLUXMOE_FFN_MTILE")) {
         const int m = std::atoi(v);
-        if (m == 16 || m == 32 || m == 64) p.m_tile = uint32_t(m);
+        if (m == 16 || m == 32 || m == 64 || (m == 256 && H % 64 == 0 && F % 64 == 0)) p.m_tile = uint32_t(m);
     }
     p.pairs_cap = uint32_t(std::max<uint64_t>(pairs, 1));
     p.tiles_cap = uint32_t(pairs / p.m_tile + groups + 1);
@@ -139,6 +141,7 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
     ks = std::min<uint64_t>(ks, 8);
     ks = std::min<uint64_t>(ks, std::max<uint64_t>(1, F / 256));
     p.ksplit = uint32_t(std::max<uint64_t>(ks, 1));
+    if (p.m_tile == 256) p.ksplit = 1;
     uint64_t o = 0;
     auto take = [&](uint64_t bytes) { uint64_t at = o; o = align_up(o + bytes, 256); return at; };
     p.off_count = take((E + 1) * 4);

@@ -68,6 +68,8 @@ def test_c1_tiny():
     dict(tokens=200, top_k=2, n_experts=3, n_slots=3),         # several row tiles per expert
     dict(tokens=33, top_k=4, hidden=136, ffn=264, n_experts=5, n_slots=5),
     dict(tokens=16, top_k=8, hidden=256, ffn=4096),            # K split of the second product
+    dict(tokens=700, top_k=2, n_experts=3, n_slots=3, hidden=192, ffn=320),   # LDS-tiled path, ragged edges
+    dict(tokens=520, top_k=1, n_experts=2, n_slots=2, hidden=256, ffn=512),   # LDS-tiled path, full tiles + tail rows
 ])
 def test_shapes(kw):
     run_ffn_case(inputs.scaled(inputs.CONFIGS["c1_tiny"], **kw), seed=1)
