@@ -344,40 +344,54 @@ __global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
 // ------------------------------------------------------------------ large row tiles (MFMA bound)
 // When an expert sees hundreds of rows (prefill-shaped batches, the shared expert) the FFN is
 // bound by the matrix cores, not by weight streaming, and operands must be reused from LDS.
-// Workgroup tile 256 rows x 256 columns, k step 64, four wavefronts in a 2 x 2 arrangement,
-// each owning 128 x 128 as 4 x 4 tiles of v_mfma_f32_32x32x16_bf16 (256 accumulator
+// Workgroup tile 256 rows x 256 columns, k step 64, eight wavefronts as 4 (rows) x 2 (columns),
+// two per SIMD so that one wavefront's LDS and barrier waits hide behind the other's MFMAs.
+// Each wavefront owns 64 x 128 as 2 x 4 tiles of v_mfma_f32_32x32x16_bf16 (128 accumulator
 // registers).  A rows (k contiguous) go to LDS as they are; B arrives row-major [k][n], so
-// each lane transposes an 8 x 8 tile in registers (v_perm_b32) and writes [n][k] rows, after
-// which both operands are read as 16-byte k-contiguous fragments.  Rows are padded by 16
-// bytes against bank conflicts; two LDS buffers, one barrier per k step, the next step's
-// global loads in flight during the current step's MFMAs.
-// MODE 1: the 256 columns are 128 of W1 and the same 128 of W3; a wavefront holds gate and up
-// values of the same elements and applies SwiGLU in registers.  MODE 2: plain product into y.
+// each lane transposes an 8 (k) x 4 (n) tile in registers (v_perm_b32) and writes [n][k] rows,
+// after which both operands are read as 16-byte k-contiguous fragments.  LDS rows are padded
+// by 16 bytes (conflict-free 16-byte reads); column c of a lane's tile goes to an LDS row
+// chosen so that the 64 lanes of a write hit consecutive rows.  Two LDS buffers, one barrier
+// per k step; the registers hold step s + 1 while step s is multiplied, are written to the
+// other buffer between the MFMAs of step s and at once reloaded with step s + 2.
+// Workgroups are numbered so that the 32 that run together on one XCD (one per CU) form a
+// 4 x 8 block of tiles and share operand slices in that XCD's L2.
+// MODE 1: the 256 tile columns are 128 of W1 and the same 128 of W3; a wavefront holds gate
+// and up values of the same elements and applies SwiGLU in registers.  MODE 2: y = h W2.
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kTM = 256, kTK = 64, kLdsPitch = kTK + 8;   // pitch in BF16 elements
+constexpr uint32_t kSuperM = 4, kSuperN = 8;              // tiles per super-tile (one XCD's 32 CUs)
 
 template <int MODE>
-__global__ __launch_bounds__(256) void gemm_tiled_kernel(FfnArgs a) {
+__global__ __launch_bounds__(512) void gemm_tiled_kernel(FfnArgs a) {
     extern __shared__ __align__(16) uint16_t lds[];
-    TileInfo t;
-    if (!tile_info(a, blockIdx.y, t)) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int q = lane & 31;
     const uint32_t K = MODE == 1 ? a.H : a.F;
     const uint32_t N = MODE == 1 ? a.F : a.H;               // columns of one B matrix
     const uint32_t ncols_tile = MODE == 1 ? 128u : 256u;     // distinct output columns per tile
-    const uint32_t n_base = blockIdx.x * ncols_tile;
-    if (n_base >= N) return;
+    const uint32_t n_ct = (N + ncols_tile - 1) / ncols_tile;
+    const uint32_t n_rt = uint32_t(a.n_tiles[0]);
+    const uint32_t n_sn = (n_ct + kSuperN - 1) / kSuperN;
+    const uint32_t xcd = blockIdx.x % 8u, jj = blockIdx.x / 8u;
+    const uint32_t st = (jj / (kSuperM * kSuperN)) * 8u + xcd;
+    const uint32_t within = jj % (kSuperM * kSuperN);
+    const uint32_t row_tile = (st / n_sn) * kSuperM + within / kSuperN;
+    const uint32_t col_tile = (st % n_sn) * kSuperN + within % kSuperN;
+    if (row_tile >= n_rt || col_tile >= n_ct) return;
+    TileInfo t;
+    if (!tile_info(a, row_tile, t)) return;
+    const uint32_t n_base = col_tile * ncols_tile;
 
-    // LDS (BF16 elements): [buffer][A tile 256 x pitch | B tile 256 x pitch]
-    constexpr int kTile = kTM * kLdsPitch;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int q = lane & 31;
+    constexpr int kTile = kTM * kLdsPitch;                   // LDS: [buffer][A tile | B tile]
 
-    // global -> register staging.  A: 8 lanes cover one row's 64 k; rows tid / 8 + 32 i.
-    const uint16_t* a_src[8];
+    // global -> register staging.  A: 8 lanes cover one row's 64 k; rows tid / 8 + 64 i.
+    const uint16_t* a_src[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int32_t r = min(int32_t(tid >> 3) + 32 * i, t.rows - 1);
+    for (int i = 0; i < 4; ++i) {
+        const int32_t r = min(int32_t(tid >> 3) + 64 * i, t.rows - 1);
         if (MODE == 1) {
             const int32_t pr = a.sorted_pair[t.row0 + r];
             a_src[i] = a.tokens + size_t(uint32_t(pr) / a.K) * a.H + 8 * (tid & 7);
@@ -385,42 +399,40 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(FfnArgs a) {
             a_src[i] = a.hbuf + size_t(t.row0 + r) * a.F + 8 * (tid & 7);
         }
     }
-    const int a_dst = (tid >> 3) * kLdsPitch + 8 * (tid & 7);          // + 32 i rows
-    // B: the lane's 8 x 8 tile: 8 consecutive columns, rows 8 (tid / 32) ..  Column c of the
-    // lane's tile goes to LDS row b_dst_row + c * b_dst_step, chosen so that the 32 lanes of a
-    // write hit consecutive rows (no bank conflicts) and so that every 32 consecutive LDS rows
-    // (one MFMA's columns) come from one matrix.
-    const uint32_t ng = tid & 31;
-    const uint32_t bk = 8u * (tid >> 5);
+    const int a_dst = (tid >> 3) * kLdsPitch + 8 * (tid & 7);          // + 64 i rows
+    // B: the lane's tile: 4 consecutive columns, 8 rows k = 8 (tid / 64) ..
+    const uint32_t cg = tid & 63;
+    const uint32_t bk = 8u * (tid >> 6);
     const uint16_t* b_src;
-    int b_dst_row, b_dst_step;
+    int b_dst_row;                                           // + c * (MODE 1 ? 32 : 64) rows
     {
         const size_t mat = size_t(a.H) * a.F;
         if (MODE == 1) {
-            const uint32_t col = min(n_base + 8u * (ng & 15u), N - 8);
-            b_src = a.slots13 + size_t(t.slot) * 2 * mat + (ng >= 16 ? mat : 0) + col;
-            b_dst_row = int(ng >> 4) * 128 + int(ng & 15);
-            b_dst_step = 16;
+            const uint32_t col = min(n_base + 4u * (cg & 31u), N - 4);
+            b_src = a.slots13 + size_t(t.slot) * 2 * mat + (cg >= 32 ? mat : 0) + col;
+            b_dst_row = int(cg >> 5) * 128 + int(cg & 31);
         } else {
-            const uint32_t col = min(n_base + 8u * ng, N - 8);
+            const uint32_t col = min(n_base + 4u * cg, N - 4);
             b_src = a.slots2 + size_t(t.slot) * mat + col;
-            b_dst_row = int(ng);
-            b_dst_step = 32;
+            b_dst_row = int(cg);
         }
     }
+    constexpr int b_dst_step = MODE == 1 ? 32 : 64;
     const int b_dst = kTile + b_dst_row * kLdsPitch + int(bk);
 
-    f32x16 acc[4][4];
+    f32x16 acc[2][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // LDS fragment offsets of this wavefront (k-contiguous 16-byte reads)
+    // LDS fragment offsets of this wavefront (k-contiguous 16-byte reads).
+    // MODE 2: B tile j = LDS rows 32 (4 wn + j) + q: column 4 (32 (j & 1) + q) + 2 wn + j / 2
+    // MODE 1: j = 0, 1 gate, j = 2, 3 up: rows 128 (j / 2) + 32 (2 wn + j % 2) + q: column 4 q + 2 wn + j % 2
     const int kfrag = 8 * (lane >> 5);
-    const int a_frag = (wm * 128 + q) * kLdsPitch + kfrag;               // + 32 i rows
+    const int a_frag = (wm * 64 + q) * kLdsPitch + kfrag;                // + 32 i rows
     int b_frag[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -428,21 +440,21 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(FfnArgs a) {
         b_frag[j] = kTile + row * kLdsPitch + kfrag;
     }
 
-    u32x4 ga[8], gb[8];
+    u32x4 ga[4];
+    u32x2 gb[8];
     const uint32_t n_steps = K / kTK;
+    auto gload = [&](uint32_t k0) __attribute__((always_inline)) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) ga[i] = *reinterpret_cast<const u32x4*>(a_src[i]);
+        for (int i = 0; i < 4; ++i) ga[i] = *reinterpret_cast<const u32x4*>(a_src[i] + k0);
 #pragma unroll
-    for (int r = 0; r < 8; ++r) gb[r] = *reinterpret_cast<const u32x4*>(b_src + size_t(bk + r) * N);
-
-    for (uint32_t s = 0; s < n_steps; ++s) {
-        uint16_t* buf = lds + (s & 1) * (2 * kTile);
-        // registers -> LDS (the buffer was last read two steps ago; a barrier lies between)
+        for (int r = 0; r < 8; ++r) gb[r] = *reinterpret_cast<const u32x2*>(b_src + size_t(k0 + bk + r) * N);
+    };
+    auto lstore = [&](uint16_t* buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<u32x4*>(buf + a_dst + 32 * i * kLdsPitch) = ga[i];
+        for (int i = 0; i < 4; ++i)
+            *reinterpret_cast<u32x4*>(buf + a_dst + 64 * i * kLdsPitch) = ga[i];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < 4; ++c) {
             u32x4 v;
             const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
             v.x = __builtin_amdgcn_perm(gb[1][c >> 1], gb[0][c >> 1], sel);
@@ -451,55 +463,65 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(FfnArgs a) {
             v.w = __builtin_amdgcn_perm(gb[7][c >> 1], gb[6][c >> 1], sel);
             *reinterpret_cast<u32x4*>(buf + b_dst + c * b_dst_step * kLdsPitch) = v;
         }
-        __syncthreads();
-        if (s + 1 < n_steps) {
-            const uint32_t k0 = (s + 1) * kTK;
+    };
+    auto mma_ks = [&](const uint16_t* buf, int ks) __attribute__((always_inline)) {
+        bf16x8 fa[2], fb[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) ga[i] = *reinterpret_cast<const u32x4*>(a_src[i] + k0);
+        for (int i = 0; i < 2; ++i)
+            fa[i] = *reinterpret_cast<const bf16x8*>(buf + a_frag + 32 * i * kLdsPitch + ks * 16);
 #pragma unroll
-            for (int r = 0; r < 8; ++r) gb[r] = *reinterpret_cast<const u32x4*>(b_src + size_t(k0 + bk + r) * N);
-        }
+        for (int j = 0; j < 4; ++j)
+            fb[j] = *reinterpret_cast<const bf16x8*>(buf + b_frag[j] + ks * 16);
 #pragma unroll
-        for (int ks = 0; ks < kTK / 16; ++ks) {
-            bf16x8 fa[4], fb[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-                fa[i] = *reinterpret_cast<const bf16x8*>(buf + a_frag + 32 * i * kLdsPitch + ks * 16);
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                fb[j] = *reinterpret_cast<const bf16x8*>(buf + b_frag[j] + ks * 16);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    };
+
+    gload(0);
+    lstore(lds);
+    if (n_steps > 1) gload(kTK);
+    __syncthreads();
+    for (uint32_t s = 0; s < n_steps; ++s) {
+        uint16_t* cur = lds + (s & 1) * (2 * kTile);
+        uint16_t* nxt = lds + ((s + 1) & 1) * (2 * kTile);
+        mma_ks(cur, 0);
+        if (s + 1 < n_steps) lstore(nxt);
+        if (s + 2 < n_steps) gload((s + 2) * kTK);
+        mma_ks(cur, 1);
+        mma_ks(cur, 2);
+        mma_ks(cur, 3);
+        __syncthreads();
     }
 
-    // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4.
-    // MODE 2: tile j of this wavefront holds column 8 q + 4 wn + j -> 4 consecutive columns per lane.
-    // MODE 1: tiles j (gate) and j + 2 (up) hold column 8 (q % 16) + 2 (2 wn + j) + q / 16.
+    // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            const int32_t row = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            const int32_t row = wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
             if (row >= t.rows) continue;
             if (MODE == 1) {
+                const uint32_t col = n_base + 4u * q + 2u * wn;      // two adjacent columns
+                if (col >= N) continue;
+                uint32_t packed = 0;
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const uint32_t col = n_base + 8u * (q & 15) + 2u * (2 * wn + j) + (q >> 4);
-                    if (col >= N) continue;
                     const float ga_ = acc[i][j][r];
                     const float up = acc[i][j + 2][r];
                     const float h = ga_ / (1.0f + __expf(-ga_)) * up;
-                    a.hbuf[size_t(t.row0 + row) * a.F + col] = uint16_t(f32_to_bf16_rne(h));
+                    packed |= f32_to_bf16_rne(h) << (16 * j);
                 }
+                *reinterpret_cast<uint32_t*>(a.hbuf + size_t(t.row0 + row) * a.F + col) = packed;
             } else {
-                const uint32_t col = n_base + 8u * q + 4u * wn;
-                if (col >= N) continue;                 // N is a multiple of 8: all 4 or none
-                *reinterpret_cast<float4*>(a.ybuf + size_t(t.row0 + row) * a.H + col) =
-                    make_float4(acc[i][0][r], acc[i][1][r], acc[i][2][r], acc[i][3][r]);
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const uint32_t col = n_base + 4u * (32 * half + q) + 2u * wn;
+                    if (col >= N) continue;
+                    *reinterpret_cast<float2*>(a.ybuf + size_t(t.row0 + row) * a.H + col) =
+                        make_float2(acc[i][half][r], acc[i][half + 2][r]);
+                }
             }
         }
 }
@@ -554,10 +576,15 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
             attr_set = true;
         }
         mark(2, 1);
-        hipLaunchKernelGGL(gemm_tiled_kernel<1>, dim3((a.F + 127) / 128, a.tiles_cap, 1), dim3(256), lds_bytes, stream, a);
+        auto grid_for = [&](uint32_t n_ct) {
+            const uint32_t n_sm = (a.tiles_cap + kSuperM - 1) / kSuperM, n_sn = (n_ct + kSuperN - 1) / kSuperN;
+            const uint32_t supers = (n_sm * n_sn + 7) / 8 * 8;      // whole rounds over the 8 XCDs
+            return dim3(supers * kSuperM * kSuperN, 1, 1);
+        };
+        hipLaunchKernelGGL(gemm_tiled_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), lds_bytes, stream, a);
         mark(2, 0);
         mark(3, 1);
-        hipLaunchKernelGGL(gemm_tiled_kernel<2>, dim3((a.H + 255) / 256, a.tiles_cap, 1), dim3(256), lds_bytes, stream, a);
+        hipLaunchKernelGGL(gemm_tiled_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), lds_bytes, stream, a);
         mark(3, 0);
         const dim3 gc2((a.H / 4 + 255) / 256, a.T, 1);
         mark(4, 1);
