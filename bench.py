@@ -33,7 +33,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="c2_mixtral", help="c1_tiny | c2_mixtral | c3_qwen3next | c4_glm45")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--ffn-rows-per-expert", type=int, default=0,
@@ -356,33 +356,32 @@ def bench_streaming(cfg, args):
 
 
 def cpu_baseline(pool, cfg, blob, w13, w2, budget_s):
-    """The oracle decoder, as it stands, on a bounded sample of the same pool (rank 0, host)."""
+    """The oracle decoder, as it stands, on a bounded sample of the same pool (rank 0, host):
+    whole tensors in blob order (down tensors of experts 0, 1, ...) until the time budget."""
     import numpy as np
     from oracle import codec
     from paper_2604_02715_amd import binding as B
     from paper_2604_02715_amd import inputs
 
     blocks = blob.numpy().reshape(-1, 4096)
-    b0, nb = B.fluxmoe_tensor_blocks(pool.ctx, 0, 2, 0)
-    lens = B.fluxmoe_code_lengths(pool.ctx, 0, 2)
-    first = B.fluxmoe_tensor_first_elems(pool.ctx, 0, 2, 0)
-    want = inputs.bits_u16(w2[0]).reshape(-1)
-    chunk = 256
-    done_blocks, elems = 0, 0
+    elems, n_blocks_done, tensors = 0, 0, 0
     t0 = time.perf_counter()
-    while done_blocks < nb and time.perf_counter() - t0 < budget_s:
-        k = min(chunk, nb - done_blocks)
-        e0, n, parts = codec.decode_blocks(blocks[b0 + done_blocks:b0 + done_blocks + k], lens)
-        for a, cnt, p in zip(e0, n, parts):
-            assert np.array_equal(p, want[a:a + cnt]), "oracle decode mismatch"
-            elems += int(cnt)
-        done_blocks += k
+    for d, arr in ((2, w2), (1, w13)):
+        lens = B.fluxmoe_code_lengths(pool.ctx, 0, d)
+        for e in range(cfg.n_experts):
+            if time.perf_counter() - t0 >= budget_s:
+                break
+            b0, nb = B.fluxmoe_tensor_blocks(pool.ctx, 0, d, e)
+            want = inputs.bits_u16(arr[e]).reshape(-1)
+            got = codec.decode_tensor(blocks[b0:b0 + nb], lens, want.size, chunk=256)
+            assert np.array_equal(got, want), "oracle decode mismatch"
+            elems += want.size
+            n_blocks_done += nb
+            tensors += 1
     dt = time.perf_counter() - t0
-    assert elems == int(first[done_blocks]) - int(first[0])
     return {"value": round(2.0 * elems / dt / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "oracle/codec.decode_blocks on the first %d of %d blocks of expert 0's down "
-                      "tensor of this pool (%d elements, %.1f s, numpy, one thread)"
-                      % (done_blocks, nb, elems, dt)}
+            "sample": "oracle/codec.decode_tensor on the first %d tensors of this pool in blob order "
+                      "(%d blocks, %d elements, %.1f s, numpy, one thread)" % (tensors, n_blocks_done, elems, dt)}
 
 
 if __name__ == "__main__":
