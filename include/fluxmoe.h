@@ -149,6 +149,21 @@ int fluxmoe_bind_layer(fluxmoe_ctx* ctx, uint32_t layer, const void* hbm_blocks,
                        uint64_t n_host_blocks, const void* host_blocks,
                        const void* check_host_copy);
 
+/*
+ * Move one whole tensor of a bound layer to another backing copy (Sec. 4.3 "Runtime
+ * adaptation": tensor-level offloading and restoration between compressed GPU memory and
+ * pinned host memory, inside a running engine).  From this call on fluxmoe_materialize reads
+ * the type-`type` tensor of `expert` from `blocks`: tier 1 = pinned host memory (fetched by
+ * DMA into the staging buffer first), tier 0 = device memory.  `blocks` holds the tensor's
+ * blocks exactly as fluxmoe_encode_pool wrote them (fluxmoe_tensor_blocks gives their range in
+ * the layer blob), 16-byte aligned.  Host state only, nothing is enqueued: work enqueued
+ * earlier still reads the previous copy, which the caller may free once that work has
+ * completed (Sec. 4.3: the retired copy is freed after the events complete).  A host-tier
+ * fetch of this layer issued before the call is forgotten.
+ */
+int fluxmoe_set_tensor_backing(fluxmoe_ctx* ctx, uint32_t layer, int type, uint32_t expert,
+                               int tier, const void* blocks);
+
 /* Bind the device staging buffer host-tier blocks are copied into before decoding
  * (two halves, used alternately by consecutive layers).  Needed only if some layer has
  * n_host_blocks > 0. */
@@ -253,6 +268,73 @@ int fluxmoe_profile_collect(fluxmoe_ctx* ctx, double out_ms[FLUXMOE_PROFILE_KIND
 int fluxmoe_shared_expert_ffn(fluxmoe_ctx* ctx, const uint16_t* w13, const uint16_t* w2,
                               const uint16_t* tokens, uint32_t T, float* out, uint32_t flags,
                               void* stream);
+
+/*
+ * Budget-aware residency planner (Sec. 4.3, Alg. 2).  Host logic only; one planner per rank.
+ * Every decoding iteration the serving loop reports the remaining batch B_rem, the active
+ * batch B_act, the measured forward latency tau_fwd and the measured materialization time of
+ * every MoE layer (any one time unit).  Every control_interval iterations with B_act > 0 the
+ * planner forms
+ *     tau_eff = (B_rem / B_act) tau_fwd,  tau_load = sum_l tau_load_layer[l],
+ *     rho = tau_eff / tau_load  (+inf when tau_load = 0)
+ * and takes one reclamation step if rho > 1 and B_act < B_rem, reverses the latest step if
+ * rho < theta, and otherwise keeps the state.  Reclamation first turns uncompressed-resident
+ * layers into pageable ones (one per step, largest index first), then offloads expert
+ * tensors to the host: ceil(AG L_r) down-projection tensors per step, and once none is left
+ * ceil(AG L_r / 2) fused gate/up tensors, each taken from the pageable layer with the smallest
+ * host-assigned volume (ties: larger layer index), largest expert index first.  The moves of a
+ * step are returned for the caller to carry out (fluxmoe_set_tensor_backing).
+ */
+typedef struct fluxmoe_planner fluxmoe_planner;
+
+typedef struct {
+    uint32_t n_layers;              /* MoE layers of this rank */
+    uint32_t experts_per_rank;      /* L_r */
+    uint32_t control_interval;      /* CI in decoding iterations (0 = 16) */
+    uint32_t reserved;              /* 0 */
+    double theta;                   /* restoration threshold in (0, 1] (0 = 0.9) */
+    double adjustment_granularity;  /* AG in (0, 1] (0 = 0.25) */
+} fluxmoe_planner_desc;
+
+typedef struct {
+    uint32_t layer;
+    uint32_t expert;                /* rank-local expert index (0 for a layer move) */
+    int32_t type;                   /* 1 fused gate/up, 2 down; 0 = the layer changes class */
+    int32_t to_host;                /* tensor: 1 to pinned host, 0 back to compressed GPU memory;
+                                       layer: 1 becomes pageable, 0 becomes uncompressed-resident */
+} fluxmoe_planner_move;
+
+#define FLUXMOE_PLAN_KEEP 0
+#define FLUXMOE_PLAN_RECLAIM 1
+#define FLUXMOE_PLAN_RESTORE (-1)
+#define FLUXMOE_PLAN_SKIP 2         /* not a control iteration, or B_act = 0 */
+#define FLUXMOE_PLAN_DONE 3         /* B_rem = 0: the run is over */
+
+typedef struct {
+    int32_t action;
+    uint32_t n_moves;
+    double rho, tau_eff, tau_load;  /* NaN unless the control rule ran */
+} fluxmoe_planner_decision;
+
+/* uncompressed: host, n_layers flags (non-zero = the layer starts uncompressed-resident), or
+ * NULL for all pageable.  All tensors start GPU-backed. */
+int fluxmoe_planner_create(const fluxmoe_planner_desc* desc, const uint8_t* uncompressed,
+                           fluxmoe_planner** out);
+int fluxmoe_planner_destroy(fluxmoe_planner* p);
+/* Largest number of moves one step can return; `moves` must hold at least that many. */
+uint32_t fluxmoe_planner_max_moves(const fluxmoe_planner* p);
+/* One decoding iteration of Alg. 2.  tau_load_layer: host, n_layers values (NULL = all 0). */
+int fluxmoe_planner_tick(fluxmoe_planner* p, uint64_t B_rem, uint64_t B_act, double tau_fwd,
+                         const double* tau_load_layer, fluxmoe_planner_decision* out,
+                         fluxmoe_planner_move* moves, size_t moves_cap);
+/* One reclamation / restoration step regardless of the control rule (n_moves 0 = nothing left). */
+int fluxmoe_planner_reclaim(fluxmoe_planner* p, fluxmoe_planner_move* moves, size_t moves_cap,
+                            uint32_t* n_moves);
+int fluxmoe_planner_restore(fluxmoe_planner* p, fluxmoe_planner_move* moves, size_t moves_cap,
+                            uint32_t* n_moves);
+/* layer_pageable: n_layers flags; on_host: [n_layers][experts_per_rank][2] flags, last index
+ * 0 = type 1, 1 = type 2.  Either may be NULL. */
+int fluxmoe_planner_state(const fluxmoe_planner* p, uint8_t* layer_pageable, uint8_t* on_host);
 
 /* Synchronous: read and clear the device error word (0 = none; bit 0 a block failed
  * validation during decode and was skipped, bit 1 an unmapped expert was routed to). */

@@ -42,6 +42,24 @@ class LayerInfo(C.Structure):
                 ("elements", C.c_uint64 * 2)]
 
 
+class PlannerDesc(C.Structure):
+    _fields_ = [("n_layers", C.c_uint32), ("experts_per_rank", C.c_uint32),
+                ("control_interval", C.c_uint32), ("reserved", C.c_uint32),
+                ("theta", C.c_double), ("adjustment_granularity", C.c_double)]
+
+
+class PlannerMove(C.Structure):
+    _fields_ = [("layer", C.c_uint32), ("expert", C.c_uint32), ("type", C.c_int32),
+                ("to_host", C.c_int32)]
+
+
+class PlannerDecision(C.Structure):
+    _fields_ = [("action", C.c_int32), ("n_moves", C.c_uint32), ("rho", C.c_double),
+                ("tau_eff", C.c_double), ("tau_load", C.c_double)]
+
+
+PLAN_KEEP, PLAN_RECLAIM, PLAN_RESTORE, PLAN_SKIP, PLAN_DONE = 0, 1, -1, 2, 3
+
 EXPORTS = {
     "fluxmoe_last_error": (C.c_char_p, []),
     "fluxmoe_create": (C.c_int, [C.POINTER(Desc), C.POINTER(C.c_void_p)]),
@@ -59,6 +77,8 @@ EXPORTS = {
     "fluxmoe_bind_arenas": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]),
     "fluxmoe_bind_layer": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint64, C.c_void_p,
                                      C.c_void_p]),
+    "fluxmoe_set_tensor_backing": (C.c_int, [C.c_void_p, C.c_uint32, C.c_int, C.c_uint32, C.c_int,
+                                             C.c_void_p]),
     "fluxmoe_bind_staging": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t]),
     "fluxmoe_reset_page_table": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
     "fluxmoe_prefetch_host": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p]),
@@ -74,6 +94,14 @@ EXPORTS = {
     "fluxmoe_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "fluxmoe_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]),
     "fluxmoe_device_errors": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
+    "fluxmoe_planner_create": (C.c_int, [C.POINTER(PlannerDesc), C.c_void_p, C.POINTER(C.c_void_p)]),
+    "fluxmoe_planner_destroy": (C.c_int, [C.c_void_p]),
+    "fluxmoe_planner_max_moves": (C.c_uint32, [C.c_void_p]),
+    "fluxmoe_planner_tick": (C.c_int, [C.c_void_p, C.c_uint64, C.c_uint64, C.c_double, C.c_void_p,
+                                       C.POINTER(PlannerDecision), C.c_void_p, C.c_size_t]),
+    "fluxmoe_planner_reclaim": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_uint32)]),
+    "fluxmoe_planner_restore": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_uint32)]),
+    "fluxmoe_planner_state": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p]),
 }
 
 
@@ -164,6 +192,10 @@ def fluxmoe_bind_layer(ctx, layer, hbm_ptr, n_host_blocks=0, host_ptr=None, chec
     _check(lib().fluxmoe_bind_layer(ctx, layer, hbm_ptr, n_host_blocks, host_ptr, check_host_copy_ptr))
 
 
+def fluxmoe_set_tensor_backing(ctx, layer, type_, expert, tier, blocks_ptr):
+    _check(lib().fluxmoe_set_tensor_backing(ctx, layer, type_, expert, tier, blocks_ptr))
+
+
 def fluxmoe_bind_staging(ctx, staging_ptr, staging_bytes):
     _check(lib().fluxmoe_bind_staging(ctx, staging_ptr, staging_bytes))
 
@@ -226,3 +258,66 @@ def fluxmoe_device_errors(ctx) -> int:
     f = C.c_uint32(0)
     _check(lib().fluxmoe_device_errors(ctx, C.byref(f)))
     return int(f.value)
+
+
+# ---------------------------------------------------------------------- residency planner
+def fluxmoe_planner_create(n_layers, experts_per_rank, control_interval=0, theta=0.0,
+                           adjustment_granularity=0.0, uncompressed=None):
+    d = PlannerDesc(n_layers, experts_per_rank, control_interval, 0, theta, adjustment_granularity)
+    h = C.c_void_p()
+    flags = None
+    if uncompressed is not None:
+        flags = np.ascontiguousarray(uncompressed, dtype=np.uint8)
+        if flags.size != n_layers:
+            raise ValueError("uncompressed must have n_layers entries")
+    _check(lib().fluxmoe_planner_create(C.byref(d), None if flags is None else flags.ctypes.data,
+                                        C.byref(h)))
+    return h
+
+
+def fluxmoe_planner_destroy(p):
+    _check(lib().fluxmoe_planner_destroy(p))
+
+
+def fluxmoe_planner_max_moves(p) -> int:
+    return int(lib().fluxmoe_planner_max_moves(p))
+
+
+def _moves_list(buf, n):
+    return [(int(m.layer), int(m.expert), int(m.type), int(m.to_host)) for m in buf[:n]]
+
+
+def fluxmoe_planner_tick(p, B_rem, B_act, tau_fwd, tau_load_layer=None):
+    """(decision, [(layer, expert, type, to_host), ...])"""
+    cap = fluxmoe_planner_max_moves(p)
+    buf = (PlannerMove * cap)()
+    dec = PlannerDecision()
+    loads = None if tau_load_layer is None else np.ascontiguousarray(tau_load_layer, dtype=np.float64)
+    _check(lib().fluxmoe_planner_tick(p, B_rem, B_act, tau_fwd,
+                                      None if loads is None else loads.ctypes.data, C.byref(dec),
+                                      C.cast(buf, C.c_void_p), cap))
+    return dec, _moves_list(buf, dec.n_moves)
+
+
+def _planner_step(fn, p):
+    cap = fluxmoe_planner_max_moves(p)
+    buf = (PlannerMove * cap)()
+    n = C.c_uint32(0)
+    _check(fn(p, C.cast(buf, C.c_void_p), cap, C.byref(n)))
+    return _moves_list(buf, n.value)
+
+
+def fluxmoe_planner_reclaim(p):
+    return _planner_step(lib().fluxmoe_planner_reclaim, p)
+
+
+def fluxmoe_planner_restore(p):
+    return _planner_step(lib().fluxmoe_planner_restore, p)
+
+
+def fluxmoe_planner_state(p, n_layers, experts_per_rank):
+    """(layer_pageable uint8 [N], on_host uint8 [N][L_r][2]; last index 0 = type 1, 1 = type 2)"""
+    pageable = np.zeros(n_layers, dtype=np.uint8)
+    on_host = np.zeros((n_layers, experts_per_rank, 2), dtype=np.uint8)
+    _check(lib().fluxmoe_planner_state(p, pageable.ctypes.data, on_host.ctypes.data))
+    return pageable, on_host

@@ -523,6 +523,16 @@ int fluxmoe_bind_layer(fluxmoe_ctx* c, uint32_t layer, const void* hbm_blocks, u
     L.hbm = static_cast<const uint8_t*>(hbm_blocks);
     L.host = static_cast<const uint8_t*>(host_blocks);
     L.n_host_blocks = n_host_blocks;
+    L.host_tensors = 0;
+    for (int ti = 0; ti < 2; ++ti)
+        for (TensorMeta& tm : L.tensors[ti]) {
+            const uint64_t a = tm.first_block, b = a + tm.n_blocks();
+            const uint64_t hb = std::min(b, std::max(a, n_host_blocks));
+            tm.n_host = hb - a;
+            tm.host_src = tm.n_host ? L.host + a * c->d.block_bytes : nullptr;
+            tm.hbm_src = hb < b ? L.hbm + (hb - n_host_blocks) * c->d.block_bytes : nullptr;
+            L.host_tensors += tm.n_host ? 1 : 0;
+        }
     L.bound = true;
     if (c->half[layer & 1].layer == int64_t(layer)) c->half[layer & 1].layer = -1;
     return FLUXMOE_OK;
@@ -535,6 +545,31 @@ int fluxmoe_bind_staging(fluxmoe_ctx* c, void* staging, size_t staging_bytes) {
     c->staging = static_cast<uint8_t*>(staging);
     c->staging_bytes = staging_bytes;
     c->half[0].layer = c->half[1].layer = -1;
+    return FLUXMOE_OK;
+}
+
+int fluxmoe_set_tensor_backing(fluxmoe_ctx* c, uint32_t layer, int type, uint32_t expert, int tier,
+                               const void* blocks) {
+    if (int rc = check_layer(c, layer, true)) return rc;
+    LayerMeta& L = c->layers[layer];
+    if (!L.bound) return set_error(FLUXMOE_ESTATE, "layer %u is not bound", layer);
+    if (type != 1 && type != 2) return set_error(FLUXMOE_EINVAL, "type must be 1 or 2");
+    if (expert >= c->d.n_experts) return set_error(FLUXMOE_ERANGE, "expert %u out of range", expert);
+    if (tier != 0 && tier != 1) return set_error(FLUXMOE_EINVAL, "tier must be 0 (HBM) or 1 (pinned host)");
+    if (!blocks || (uintptr_t(blocks) & 15)) return set_error(FLUXMOE_EINVAL, "blocks must be non-NULL, 16-byte aligned");
+    TensorMeta& tm = L.tensors[type - 1][expert];
+    L.host_tensors -= tm.n_host ? 1 : 0;
+    if (tier == 1) {
+        tm.n_host = tm.n_blocks();
+        tm.host_src = static_cast<const uint8_t*>(blocks);
+        tm.hbm_src = nullptr;
+    } else {
+        tm.n_host = 0;
+        tm.host_src = nullptr;
+        tm.hbm_src = static_cast<const uint8_t*>(blocks);
+    }
+    L.host_tensors += tm.n_host ? 1 : 0;
+    if (c->half[layer & 1].layer == int64_t(layer)) c->half[layer & 1].layer = -1;   // staged copies are stale
     return FLUXMOE_OK;
 }
 
@@ -570,32 +605,32 @@ static int stage_host_blocks(fluxmoe_ctx* c, uint32_t layer, const int32_t* ids,
     st.layer = -1;
     st.off[0].assign(c->d.n_experts, -1);
     st.off[1].assign(c->d.n_experts, -1);
-    if (L.n_host_blocks == 0) { st.layer = layer; return FLUXMOE_OK; }
+    if (L.host_tensors == 0) { st.layer = layer; return FLUXMOE_OK; }
     if (!c->staging) return set_error(FLUXMOE_ESTATE, "layer %u has host-tier blocks but no staging buffer is bound", layer);
     const uint32_t B = c->d.block_bytes;
     const uint64_t half_bytes = (c->staging_bytes / 2) / B * B;
     uint8_t* base = c->staging + h * half_bytes;
     std::vector<int32_t> sorted(ids, ids + n);
     std::sort(sorted.begin(), sorted.end());
-    struct Range { uint64_t a, b, dst; };
-    std::vector<Range> ranges;
+    struct Range { const uint8_t* src; uint64_t bytes, dst; };
+    std::vector<Range> ranges;               // adjacent source ranges are merged into one copy
     uint64_t cursor = 0;
     for (int ti : {1, 0})
         for (int32_t e : sorted) {
             const TensorMeta& tm = L.tensors[ti][e];
-            const uint64_t a = tm.first_block, b = std::min<uint64_t>(tm.first_block + tm.n_blocks(), L.n_host_blocks);
-            if (a >= b) continue;
+            if (tm.n_host == 0) continue;
             st.off[ti][e] = int64_t(cursor);
-            if (!ranges.empty() && ranges.back().b == a) ranges.back().b = b;
-            else ranges.push_back({a, b, cursor});
-            cursor += (b - a) * B;
+            const uint64_t bytes = tm.n_host * B;
+            if (!ranges.empty() && ranges.back().src + ranges.back().bytes == tm.host_src) ranges.back().bytes += bytes;
+            else ranges.push_back({tm.host_src, bytes, cursor});
+            cursor += bytes;
         }
     if (cursor > half_bytes)
         return set_error(FLUXMOE_ENOMEM, "staging half holds %llu bytes, layer %u needs %llu",
                          (unsigned long long)half_bytes, layer, (unsigned long long)cursor);
     if (c->half_done_valid[h]) HIPCHECK(hipStreamWaitEvent(s, c->ev_half_done[h], 0));
     for (const Range& r : ranges)
-        HIPCHECK(hipMemcpyAsync(base + r.dst, L.host + r.a * B, (r.b - r.a) * B, hipMemcpyHostToDevice, s));
+        HIPCHECK(hipMemcpyAsync(base + r.dst, r.src, r.bytes, hipMemcpyHostToDevice, s));
     HIPCHECK(hipEventRecord(c->ev_copied[h], s));
     st.layer = layer;
     return FLUXMOE_OK;
@@ -633,14 +668,14 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
     bool need_host = false;
     for (uint32_t i = 0; i < n && !need_host; ++i)
         for (int ti = 0; ti < 2; ++ti)
-            if (L.tensors[ti][expert_ids[i]].first_block < L.n_host_blocks) need_host = true;
+            if (L.tensors[ti][expert_ids[i]].n_host) need_host = true;
     bool wait_copy = false;
     if (need_host) {
         StageHalf& st = c->half[layer & 1];
         bool staged = st.layer == int64_t(layer);
         for (uint32_t i = 0; i < n && staged; ++i)
             for (int ti = 0; ti < 2; ++ti)
-                if (L.tensors[ti][expert_ids[i]].first_block < L.n_host_blocks && st.off[ti][expert_ids[i]] < 0)
+                if (L.tensors[ti][expert_ids[i]].n_host && st.off[ti][expert_ids[i]] < 0)
                     staged = false;
         if (!staged) {
             if (int rc = stage_host_blocks(c, layer, expert_ids, n, stream)) return rc;
@@ -669,20 +704,18 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
         uint8_t* arena = ti == 0 ? c->slots13 : c->slots2;
         for (uint32_t i = 0; i < n; ++i) {
             const TensorMeta& tm = L.tensors[ti][expert_ids[i]];
-            const uint64_t a = tm.first_block, b = tm.first_block + tm.n_blocks();
-            const uint64_t hb = std::min(b, std::max(a, L.n_host_blocks));   // host part is [a, hb)
+            const uint64_t nb = tm.n_blocks(), nh = tm.n_host;     // host part is the first nh blocks
             const uint64_t dst = uint64_t(uintptr_t(arena)) + uint64_t(dst_slots[i]) * sigma;
-            if (hb > a) {
+            if (nh) {
                 const uint8_t* src = c->staging + half * half_bytes + c->half[half].off[ti][expert_ids[i]];
-                jobs[nj++] = DecodeJob{uint64_t(uintptr_t(src)), dst, blocks, uint32_t(hb - a),
+                jobs[nj++] = DecodeJob{uint64_t(uintptr_t(src)), dst, blocks, uint32_t(nh),
                                        uint32_t(ti == 0 ? c->elems13 : c->elems2), 0};
-                blocks += uint32_t(hb - a);
+                blocks += uint32_t(nh);
             }
-            if (b > hb) {
-                const uint8_t* src = L.hbm + (hb - L.n_host_blocks) * B;
-                jobs[nj++] = DecodeJob{uint64_t(uintptr_t(src)), dst, blocks, uint32_t(b - hb),
+            if (nb > nh) {
+                jobs[nj++] = DecodeJob{uint64_t(uintptr_t(tm.hbm_src)), dst, blocks, uint32_t(nb - nh),
                                        uint32_t(ti == 0 ? c->elems13 : c->elems2), 0};
-                blocks += uint32_t(b - hb);
+                blocks += uint32_t(nb - nh);
             }
         }
         cmd->n_jobs[ti] = nj;

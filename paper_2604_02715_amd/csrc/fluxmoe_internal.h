@@ -22,6 +22,11 @@ struct TensorMeta {
     uint64_t first_block = 0;            // index in the layer blob
     std::vector<uint32_t> first_elem;    // [n_blocks + 1]
     uint64_t n_blocks() const { return first_elem.empty() ? 0 : first_elem.size() - 1; }
+    // tier backing, set by fluxmoe_bind_layer and changed by fluxmoe_set_tensor_backing:
+    // the tensor's blocks [0, n_host) are read from host_src, the rest from hbm_src
+    uint64_t n_host = 0;
+    const uint8_t* host_src = nullptr;   // pinned address of the tensor's block 0
+    const uint8_t* hbm_src = nullptr;    // device address of the tensor's block n_host
 };
 
 struct LayerMeta {
@@ -35,6 +40,7 @@ struct LayerMeta {
     const uint8_t* hbm = nullptr;        // device pointer to block n_host_blocks
     const uint8_t* host = nullptr;       // pinned pointer to block 0
     uint64_t n_host_blocks = 0;
+    uint64_t host_tensors = 0;           // tensors with n_host > 0
 };
 
 // Encode one flat tensor into consecutive blocks at dst (plan must come from plan_tensor).

@@ -38,6 +38,7 @@ class ExpertPool:
         self.host_blobs = {}
         self.staging = None
         self.blob_bytes = {}
+        self.tensor_copies = {}
 
     def close(self):
         if self.ctx is not None:
@@ -77,6 +78,22 @@ class ExpertPool:
         B.fluxmoe_bind_layer(self.ctx, layer, dev_part.data_ptr() if dev_part.numel() else None,
                              n_host, host_ptr, blob.data_ptr() if check else None)
         return n_blocks, n_host
+
+    def set_tensor_backing(self, layer, type_, expert, to_host: bool, blob: torch.Tensor):
+        """Carry out one tensor move of the residency planner (Sec. 4.3): copy the tensor's blocks
+        out of the layer blob (CPU uint8) into pinned host or device memory and re-point the
+        library at that copy.  The previous copy is dropped after a device synchronisation."""
+        Bk = self.cfg_block_bytes
+        first, nb = B.fluxmoe_tensor_blocks(self.ctx, layer, type_, expert)
+        part = blob[first * Bk:(first + nb) * Bk]
+        if to_host:
+            copy = torch.empty(nb * Bk, dtype=torch.uint8, pin_memory=True)
+            copy.copy_(part)
+        else:
+            copy = part.to(self.device)
+        B.fluxmoe_set_tensor_backing(self.ctx, layer, type_, expert, 1 if to_host else 0, copy.data_ptr())
+        torch.cuda.synchronize()
+        self.tensor_copies[(layer, type_, expert)] = copy
 
     @property
     def cfg_block_bytes(self):
