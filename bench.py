@@ -39,6 +39,16 @@ def main():
     ap.add_argument("--ffn-rows-per-expert", type=int, default=0,
                     help="FFN-only sweep point: balanced routing with this many rows per expert "
                          "(prefill-shaped batch) on the config's layer shape; reports TFLOP/s")
+    ap.add_argument("--placement", default="prefix",
+                    help="c5_stream only: how each layer is split between HBM and pinned host memory: "
+                         "prefix (the config's block fraction) | hbm | balanced (measured "
+                         "beta_cpu / (beta_gpu + beta_cpu), whole down tensors) | budget (--host-budget as "
+                         "whole down tensors in every layer) | whole_layer (the last layers entirely on the "
+                         "host, same budget) | all")
+    ap.add_argument("--small", action="store_true",
+                    help="c5_stream only: a reduced copy of the config (quick functional run, not a result)")
+    ap.add_argument("--host-budget", type=float, default=0.125,
+                    help="host share of the routed-expert weights for --placement budget / whole_layer")
     ap.add_argument("--exp3", action="store_true",
                     help="standalone decompression in the paper's Exp#3 setting: one GPU's rank-local "
                          "shard of one layer per run, latency mean/std/P99 over repetitions")
@@ -60,6 +70,9 @@ def main():
         return bench_exp3(args)
     cfg = inputs.CONFIGS[args.config]
     if cfg.n_layers > 1:
+        if args.small:
+            cfg = inputs.scaled(cfg, name=cfg.name + "_small", n_experts=16, hidden=512, ffn=768, tokens=64,
+                                top_k=4, n_slots=12, n_layers=6)
         return bench_streaming(cfg, args)
     if args.ffn_rows_per_expert:
         return bench_ffn_rows(cfg, args)
@@ -320,99 +333,195 @@ def bench_ffn_rows(cfg, args):
 
 
 def bench_streaming(cfg, args):
-    """Config 5: all layers in order, 60 % of each layer's blocks in HBM, 40 % in pinned host
-    memory fetched on a side stream, two slot halves; steady-state time per layer."""
+    """Config 5: all layers in order through two slot halves, part of every layer's compressed
+    blocks in pinned host memory fetched on a side stream; steady-state time per layer.
+    --placement selects the tier split (Sec. 4.2 "Memory hierarchy model" and the whole-layer
+    ablation of Sec. 6.1)."""
+    import math
+
     import numpy as np
     import torch
     from paper_2604_02715_amd import binding as B
     from paper_2604_02715_amd import harness, inputs
 
     t0 = time.time()
+    placements = (["hbm", "balanced", "budget", "whole_layer", "prefix"] if args.placement == "all"
+                  else args.placement.split(","))
     pool = harness.ExpertPool(cfg)
-    stats = []
+    blobs = {}
     for layer in range(cfg.n_layers):
         w13, w2 = harness.make_layer_on_host(cfg, layer, 0, gen_device="cuda")
         blob = pool.encode_layer(layer, w13, w2)
-        stats.append(pool.bind_layer(layer, blob, cfg.host_fraction, check=(layer == 0)))
+        blobs[layer] = blob.clone()
         del w13, w2, blob
-        print("layer %d encoded and bound: %d blocks, %d in pinned host (%.0f s)"
-              % (layer, stats[-1][0], stats[-1][1], time.time() - t0), file=sys.stderr, flush=True)
-    pool.bind_staging(2 * max(s[1] for s in stats) * 4096 + 8192)
+        print("layer %d encoded (%.0f s)" % (layer, time.time() - t0), file=sys.stderr, flush=True)
     routings = [inputs.routing(cfg, layer) for layer in range(cfg.n_layers)]
     xs = [inputs.activations(cfg, layer).cuda() for layer in range(cfg.n_layers)]
     outs = [torch.zeros((cfg.tokens, cfg.hidden), dtype=torch.float32, device="cuda") for _ in xs]
-    proxy = harness.StreamingProxy(pool, routings, xs, outs)
-    pool.reset_page_table()
-    setup_s = time.time() - t0
+    dense_layer = cfg.n_experts * (cfg.sigma1 + cfg.sigma2)
+    E = cfg.n_experts
 
-    # parity on the fly: one overlapped pass, then the slots of the last two layers' last waves
-    # still hold their experts; compare them with regenerated originals
-    proxy.run_pass()
-    torch.cuda.synchronize()
-    assert pool.device_errors() == 0
-    if not args.no_check:
-        for layer in (cfg.n_layers - 2, cfg.n_layers - 1):
-            w13, w2 = inputs.layer_weights(cfg, layer, device="cuda")
-            w, slots = proxy.plan[layer][1][-1]
-            for e, s in zip(w, slots):
-                assert torch.equal(pool.slot13(int(s)), w13[int(e)].reshape(-1).view(torch.int16)), "decode mismatch"
-                assert torch.equal(pool.slot2(int(s)), w2[int(e)].reshape(-1).view(torch.int16)), "decode mismatch"
-            del w13, w2
+    def measure_betas():
+        """beta_gpu: dense BF16 bytes per second of decoding HBM-resident blocks; beta_cpu: the
+        same for host-tier blocks, i.e. the pinned-host DMA rate divided by the pool's
+        compressed/dense ratio."""
+        pool.bind_layer(0, blobs[0], 0.0, check=False)
+        pool.reset_page_table()
+        half = cfg.n_slots // 2
+        ids = list(range(half))
+        B.fluxmoe_profile_enable(pool.ctx, True)
+        for i in range(6):
+            if i == 1:
+                torch.cuda.synchronize()
+                B.fluxmoe_profile_collect(pool.ctx)
+            pool.materialize(0, ids, ids)
+        torch.cuda.synchronize()
+        ms, n = B.fluxmoe_profile_collect(pool.ctx)["decode"]
+        B.fluxmoe_profile_enable(pool.ctx, False)
+        beta_gpu = half * (cfg.sigma1 + cfg.sigma2) / (ms / n * 1e-3)
+        nbytes = min(1 << 29, blobs[0].numel())
+        src = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        src.copy_(blobs[0][:nbytes])
+        dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src, non_blocking=True)
+        a.record()
+        for _ in range(3):
+            dst.copy_(src, non_blocking=True)
+        b.record()
+        torch.cuda.synchronize()
+        pcie = 3 * nbytes / (a.elapsed_time(b) * 1e-3)
+        ratio = pool.blob_bytes[0] / dense_layer
+        del src, dst
+        return beta_gpu, pcie / ratio, pcie
 
-    def timed_passes(n_pass, **kw):
-        per_layer = []
-        for _ in range(n_pass):
-            evs = [torch.cuda.Event(enable_timing=True) for _ in range(cfg.n_layers)]
-            proxy.run_pass(layer_done_events=evs, **kw)
-            torch.cuda.synchronize()
-            per_layer.append([evs[i - 1].elapsed_time(evs[i]) for i in range(1, cfg.n_layers)])
-        return np.asarray(per_layer)
+    def host_tensors_of(n_down, n_fused):
+        """Largest expert indices first (the planner's order, Sec. 4.3)."""
+        return [(2, e) for e in range(E - n_down, E)] + [(1, e) for e in range(E - n_fused, E)]
 
-    for _ in range(args.warmup if args.warmup < 3 else 1):
+    streams = None
+    for placement in placements:
+        t1 = time.time()
+        pool.host_blobs.clear()
+        pool.tensor_copies.clear()
+        torch.cuda.synchronize()
+        if hasattr(torch._C, "_host_emptyCache"):
+            torch._C._host_emptyCache()                      # give pinned buffers of the last placement back
+        info = {"placement": placement}
+        host_bytes = []
+        if placement == "balanced":
+            beta_gpu, beta_cpu, pcie = measure_betas()
+            x_bw, n_down, n_fused = B.fluxmoe_balanced_split(beta_gpu, beta_cpu, E)
+            info.update(beta_gpu_GBps=round(beta_gpu / 1e9, 1), beta_cpu_GBps=round(beta_cpu / 1e9, 1),
+                        pcie_GBps=round(pcie / 1e9, 1), x_bw=round(x_bw, 5), host_down_tensors=n_down,
+                        host_fused_tensors=n_fused, x_realised=round((n_down + 2 * n_fused) / (3 * E), 5))
+        elif placement == "budget":
+            units = math.ceil(3 * E * args.host_budget - 1e-12)
+            n_down = min(units, E)
+            n_fused = min(E, (units - n_down + 1) // 2)
+            info.update(host_budget=args.host_budget, host_down_tensors=n_down, host_fused_tensors=n_fused,
+                        x_realised=round((n_down + 2 * n_fused) / (3 * E), 5))
+        n_host_layers = math.ceil(args.host_budget * cfg.n_layers - 1e-12) if placement == "whole_layer" else 0
+        for layer in range(cfg.n_layers):
+            frac = {"prefix": cfg.host_fraction, "whole_layer": 1.0 if layer >= cfg.n_layers - n_host_layers else 0.0}.get(placement, 0.0)
+            _, n_host = pool.bind_layer(layer, blobs[layer], frac, check=(layer == 0))
+            hb = n_host * 4096
+            if placement in ("balanced", "budget"):
+                hb = pool.place_tensors_on_host(layer, blobs[layer], host_tensors_of(n_down, n_fused))
+            host_bytes.append(hb)
+        if placement == "whole_layer":
+            info.update(host_budget=args.host_budget, host_layers=n_host_layers)
+        if max(host_bytes) > 0:
+            pool.bind_staging(2 * max(host_bytes) + 8192)
+        proxy = harness.StreamingProxy(pool, routings, xs, outs, streams=streams)
+        streams = (proxy.load_stream, proxy.infer_stream, proxy.copy_stream)
+        pool.reset_page_table()
+        setup_s = time.time() - t1
+        print("placement %s bound (%.0f s)" % (placement, setup_s), file=sys.stderr, flush=True)
+
+        # parity on the fly: one overlapped pass, then the slots of the last two layers' last waves
+        # still hold their experts; compare them with regenerated originals
         proxy.run_pass()
-    torch.cuda.synchronize()
-    n_pass = max(1, min(args.steps, 5))
-    t1 = time.perf_counter()
-    pl = timed_passes(n_pass)
-    wall = time.perf_counter() - t1
-    steady = pl[:, 1:]                                   # layers 2..N-1 of every pass
-    per_layer_ms = float(steady.mean())
+        torch.cuda.synchronize()
+        assert pool.device_errors() == 0
+        if not args.no_check:
+            for layer in (cfg.n_layers - 2, cfg.n_layers - 1):
+                w13, w2 = inputs.layer_weights(cfg, layer, device="cuda")
+                w, slots = proxy.plan[layer][1][-1]
+                for e, s_ in zip(w, slots):
+                    assert torch.equal(pool.slot13(int(s_)), w13[int(e)].reshape(-1).view(torch.int16)), "decode mismatch"
+                    assert torch.equal(pool.slot2(int(s_)), w2[int(e)].reshape(-1).view(torch.int16)), "decode mismatch"
+                del w13, w2
 
-    # isolated components per layer (layer 2 as the sample): host fetch, decode, FFN
-    B.fluxmoe_profile_enable(pool.ctx, True)
-    B.fluxmoe_profile_collect(pool.ctx)
-    proxy.run_pass(single_stream=True)
-    torch.cuda.synchronize()
-    prof = B.fluxmoe_profile_collect(pool.ctx)
-    B.fluxmoe_profile_enable(pool.ctx, False)
-    decode_ms = prof["decode"][0] / cfg.n_layers
-    ffn_ms = sum(prof[k][0] for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")) / cfg.n_layers
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record(proxy.copy_stream)
-    pool.prefetch_host(2, proxy.plan[2][0], proxy.copy_stream)
-    ev1.record(proxy.copy_stream)
-    torch.cuda.synchronize()
-    copy_ms = ev0.elapsed_time(ev1)
-    union = np.mean([len(u) for u, _ in proxy.plan])
-    host_bytes = float(np.mean([s[1] for s in stats])) * 4096 * union / cfg.n_experts
-    dense_bytes = union * (cfg.sigma1 + cfg.sigma2)
-    result = {
-        "metric": "streaming_steady_state_per_layer", "value": round(per_layer_ms, 3), "unit": "ms",
-        "n_gpus": 1, "steps": n_pass, "warmup": 1, "ms_per_step": round(wall / n_pass * 1e3, 2),
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": cfg.name, "layers": cfg.n_layers, "experts": cfg.n_experts, "hidden": cfg.hidden,
-                   "ffn": cfg.ffn, "tokens": cfg.tokens, "top_k": cfg.top_k, "slots": cfg.n_slots,
-                   "host_fraction": cfg.host_fraction, "mean_routed_union": round(float(union), 1),
-                   "waves_per_layer": round(float(np.mean([len(w) for _, w in proxy.plan])), 2)},
-        "per_layer": {"steady_ms_mean": round(per_layer_ms, 3), "steady_ms_std": round(float(steady.std()), 3),
-                      "host_fetch_ms_isolated": round(copy_ms, 3), "decode_ms_isolated": round(decode_ms, 3),
-                      "ffn_ms_isolated": round(ffn_ms, 3),
-                      "pcie_GBps": round(host_bytes / (copy_ms * 1e-3) / 1e9, 1),
-                      "overlap_efficiency": round(max(copy_ms, decode_ms + ffn_ms) / per_layer_ms, 3),
-                      "dense_out_GBps": round(dense_bytes / (per_layer_ms * 1e-3) / 1e9, 1)},
-        "setup_s": round(setup_s, 1),
-    }
-    print(json.dumps(result), flush=True)
+        def timed_passes(n_pass, **kw):
+            per_layer, whole = [], []
+            for _ in range(n_pass):
+                evs = [torch.cuda.Event(enable_timing=True) for _ in range(cfg.n_layers)]
+                start = torch.cuda.Event(enable_timing=True)
+                start.record(proxy.infer_stream)
+                proxy.run_pass(layer_done_events=evs, **kw)
+                torch.cuda.synchronize()
+                per_layer.append([evs[i - 1].elapsed_time(evs[i]) for i in range(1, cfg.n_layers)])
+                whole.append(start.elapsed_time(evs[-1]))
+            return np.asarray(per_layer), np.asarray(whole)
+
+        for _ in range(args.warmup if args.warmup < 3 else 1):
+            proxy.run_pass()
+        torch.cuda.synchronize()
+        n_pass = max(1, min(args.steps, 5))
+        t2 = time.perf_counter()
+        pl, whole = timed_passes(n_pass)
+        wall = time.perf_counter() - t2
+        steady = pl[:, 1:]                                   # layers 2..N-1 of every pass
+        per_layer_ms = float(steady.mean())
+
+        # isolated components per layer: host fetch (layer with the most host bytes), decode, FFN
+        B.fluxmoe_profile_enable(pool.ctx, True)
+        B.fluxmoe_profile_collect(pool.ctx)
+        proxy.run_pass(single_stream=True)
+        torch.cuda.synchronize()
+        prof = B.fluxmoe_profile_collect(pool.ctx)
+        B.fluxmoe_profile_enable(pool.ctx, False)
+        decode_ms = prof["decode"][0] / cfg.n_layers
+        ffn_ms = sum(prof[k][0] for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")) / cfg.n_layers
+        copy_ms, pcie_rate = 0.0, None
+        if max(host_bytes) > 0:
+            hl = int(np.argmax(host_bytes))
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record(proxy.copy_stream)
+            pool.prefetch_host(hl, proxy.plan[hl][0], proxy.copy_stream)
+            ev1.record(proxy.copy_stream)
+            torch.cuda.synchronize()
+            copy_ms = ev0.elapsed_time(ev1)
+            if placement in ("prefix", "whole_layer"):
+                fetched = host_bytes[hl] * len(proxy.plan[hl][0]) / E
+            else:
+                fetched = sum(B.fluxmoe_tensor_blocks(pool.ctx, hl, t, e)[1] * 4096
+                              for (t, e) in host_tensors_of(n_down, n_fused) if e in set(int(v) for v in proxy.plan[hl][0]))
+            pcie_rate = round(fetched / (copy_ms * 1e-3) / 1e9, 1)
+        union = np.mean([len(u) for u, _ in proxy.plan])
+        dense_bytes = union * (cfg.sigma1 + cfg.sigma2)
+        result = {
+            "metric": "streaming_steady_state_per_layer", "value": round(per_layer_ms, 3), "unit": "ms",
+            "n_gpus": 1, "steps": n_pass, "warmup": 1, "ms_per_step": round(wall / n_pass * 1e3, 2),
+            "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": cfg.name, "layers": cfg.n_layers, "experts": cfg.n_experts, "hidden": cfg.hidden,
+                       "ffn": cfg.ffn, "tokens": cfg.tokens, "top_k": cfg.top_k, "slots": cfg.n_slots,
+                       "host_share_of_pool": round(sum(host_bytes) / sum(pool.blob_bytes.values()), 4),
+                       "mean_routed_union": round(float(union), 1),
+                       "waves_per_layer": round(float(np.mean([len(w) for _, w in proxy.plan])), 2), **info},
+            "per_layer": {"steady_ms_mean": round(per_layer_ms, 3), "steady_ms_std": round(float(steady.std()), 3),
+                          "steady_ms_max": round(float(steady.max()), 3),
+                          "pass_ms_over_layers": round(float(whole.mean()) / cfg.n_layers, 3),
+                          "host_fetch_ms_isolated": round(copy_ms, 3), "decode_ms_isolated": round(decode_ms, 3),
+                          "ffn_ms_isolated": round(ffn_ms, 3), "pcie_GBps": pcie_rate,
+                          "overlap_efficiency": (round(max(copy_ms, decode_ms + ffn_ms) / per_layer_ms, 3)
+                                                 if placement != "whole_layer" else None),
+                          "dense_out_GBps": round(dense_bytes / (per_layer_ms * 1e-3) / 1e9, 1)},
+            "setup_s": round(setup_s + (t1 - t0 if placement == placements[0] else 0), 1),
+        }
+        print(json.dumps(result), flush=True)
+        del proxy
     pool.close()
 
 

@@ -336,6 +336,19 @@ int fluxmoe_planner_restore(fluxmoe_planner* p, fluxmoe_planner_move* moves, siz
  * 0 = type 1, 1 = type 2.  Either may be NULL. */
 int fluxmoe_planner_state(const fluxmoe_planner* p, uint8_t* layer_pageable, uint8_t* on_host);
 
+/*
+ * Bandwidth-balanced tier split (Sec. 4.2 "Memory hierarchy model").  With the two backends
+ * materializing their shares of a layer concurrently at effective rates beta_gpu and beta_cpu
+ * (any one unit, in dense BF16 bytes per time), both finish together when the host share is
+ *     x_bw = beta_cpu / (beta_gpu + beta_cpu).
+ * It is realised with whole tensors: ceil(3 L_r x_bw) down-projection tensors (a layer is
+ * 3 L_r down-projection volumes), so the realised share exceeds x_bw by less than 1/(3 L_r).
+ * If that count exceeds L_r (x_bw > 1/3) the remainder is taken as fused tensors, two volumes
+ * each, rounded upward.  Host only; output pointers may be NULL.
+ */
+int fluxmoe_balanced_split(double beta_gpu, double beta_cpu, uint32_t experts_per_rank,
+                           double* x_bw, uint32_t* n_down, uint32_t* n_fused);
+
 /* Synchronous: read and clear the device error word (0 = none; bit 0 a block failed
  * validation during decode and was skipped, bit 1 an unmapped expert was routed to). */
 int fluxmoe_device_errors(fluxmoe_ctx* ctx, uint32_t* out_flags);

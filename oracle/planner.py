@@ -118,3 +118,17 @@ class Planner:
             changed = self.restore()
             return (RESTORE if changed else KEEP), r, changed
         return KEEP, r, []
+
+
+def balanced_split(beta_gpu: float, beta_cpu: float, L_r: int):
+    """Sec. 4.2 "Memory hierarchy model": the CPU share that equalises the two backends' times is
+    x_bw = beta_cpu / (beta_gpu + beta_cpu); a layer's BF16 volume is 3 L_r down-projection
+    tensors (sigma_1 = 2 sigma_2), so the target is 3 L_r x_bw down tensors, rounded upward.
+    Returns (x_bw, n_down, n_fused, x_realised).  Reading for x_bw > 1/3, which the paper says
+    does not occur in its deployments: all L_r down tensors, then fused tensors (2 units each),
+    rounded upward again."""
+    x_bw = beta_cpu / (beta_gpu + beta_cpu)
+    units = math.ceil(3 * L_r * x_bw - 1e-12)
+    n_down = min(units, L_r)
+    n_fused = min(L_r, math.ceil((units - n_down) / 2))
+    return x_bw, n_down, n_fused, (n_down + 2 * n_fused) / (3 * L_r)

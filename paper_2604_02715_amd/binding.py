@@ -94,6 +94,8 @@ EXPORTS = {
     "fluxmoe_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "fluxmoe_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]),
     "fluxmoe_device_errors": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
+    "fluxmoe_balanced_split": (C.c_int, [C.c_double, C.c_double, C.c_uint32, C.POINTER(C.c_double),
+                                         C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]),
     "fluxmoe_planner_create": (C.c_int, [C.POINTER(PlannerDesc), C.c_void_p, C.POINTER(C.c_void_p)]),
     "fluxmoe_planner_destroy": (C.c_int, [C.c_void_p]),
     "fluxmoe_planner_max_moves": (C.c_uint32, [C.c_void_p]),
@@ -321,3 +323,11 @@ def fluxmoe_planner_state(p, n_layers, experts_per_rank):
     on_host = np.zeros((n_layers, experts_per_rank, 2), dtype=np.uint8)
     _check(lib().fluxmoe_planner_state(p, pageable.ctypes.data, on_host.ctypes.data))
     return pageable, on_host
+
+
+def fluxmoe_balanced_split(beta_gpu, beta_cpu, experts_per_rank):
+    """(x_bw, n_down, n_fused)"""
+    x, nd, nf = C.c_double(), C.c_uint32(), C.c_uint32()
+    _check(lib().fluxmoe_balanced_split(beta_gpu, beta_cpu, experts_per_rank, C.byref(x), C.byref(nd),
+                                        C.byref(nf)))
+    return float(x.value), int(nd.value), int(nf.value)

@@ -100,6 +100,22 @@ int check(const fluxmoe_planner* p, const void* moves, size_t cap) {
 
 extern "C" {
 
+int fluxmoe_balanced_split(double beta_gpu, double beta_cpu, uint32_t experts_per_rank, double* x_bw,
+                           uint32_t* n_down, uint32_t* n_fused) {
+    if (!(beta_gpu > 0) || !(beta_cpu >= 0) || !std::isfinite(beta_gpu) || !std::isfinite(beta_cpu))
+        return set_error(FLUXMOE_EINVAL, "bandwidths must be finite, beta_gpu > 0, beta_cpu >= 0");
+    if (experts_per_rank == 0) return set_error(FLUXMOE_EINVAL, "experts_per_rank must be positive");
+    const double x = beta_cpu / (beta_gpu + beta_cpu);
+    // a layer is 3 L_r down-projection volumes (a fused tensor is two of them)
+    const uint64_t units = uint64_t(std::ceil(3.0 * experts_per_rank * x - 1e-12));
+    const uint64_t down = std::min<uint64_t>(units, experts_per_rank);
+    const uint64_t fused = std::min<uint64_t>(experts_per_rank, (units - down + 1) / 2);
+    if (x_bw) *x_bw = x;
+    if (n_down) *n_down = uint32_t(down);
+    if (n_fused) *n_fused = uint32_t(fused);
+    return FLUXMOE_OK;
+}
+
 int fluxmoe_planner_create(const fluxmoe_planner_desc* d, const uint8_t* uncompressed,
                            fluxmoe_planner** out) {
     if (!d || !out) return set_error(FLUXMOE_EINVAL, "NULL argument");

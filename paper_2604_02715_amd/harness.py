@@ -95,6 +95,26 @@ class ExpertPool:
         torch.cuda.synchronize()
         self.tensor_copies[(layer, type_, expert)] = copy
 
+    def place_tensors_on_host(self, layer, blob: torch.Tensor, tensors):
+        """Whole-tensor host placement of a bound layer (Sec. 4.2: the bandwidth-balanced split is
+        realised with whole down-projection tensors): the listed (type, expert) tensors are packed
+        into one pinned buffer, down tensors first, each group by ascending expert, so that the
+        staging copy of a routed set is a few long DMAs.  Returns the pinned bytes."""
+        Bk = self.cfg_block_bytes
+        order = sorted(tensors, key=lambda te: (-te[0], te[1]))
+        ranges = [B.fluxmoe_tensor_blocks(self.ctx, layer, t, e) for (t, e) in order]
+        total = sum(nb for _, nb in ranges) * Bk
+        if total == 0:
+            return 0
+        pinned = torch.empty(total, dtype=torch.uint8, pin_memory=True)
+        at = 0
+        for (t, e), (first, nb) in zip(order, ranges):
+            pinned[at:at + nb * Bk].copy_(blob[first * Bk:(first + nb) * Bk])
+            B.fluxmoe_set_tensor_backing(self.ctx, layer, t, e, 1, pinned.data_ptr() + at)
+            at += nb * Bk
+        self.host_blobs[layer] = pinned
+        return total
+
     @property
     def cfg_block_bytes(self):
         return 4096
@@ -168,7 +188,7 @@ class StreamingProxy:
     library's (events inside fluxmoe_materialize / fluxmoe_expert_ffn / fluxmoe_prefetch_host).
     """
 
-    def __init__(self, pool: ExpertPool, routings, xs, outs, seed=0):
+    def __init__(self, pool: ExpertPool, routings, xs, outs, seed=0, streams=None):
         cfg = pool.cfg
         self.pool, self.cfg = pool, cfg
         self.xs, self.outs = xs, outs
@@ -185,9 +205,11 @@ class StreamingProxy:
                 perm = inputs.slot_permutation(self.half, cfg.name, seed, layer, w0)[:len(w)]
                 waves.append((np.asarray(w, dtype=np.int32), (base + perm).astype(np.int32)))
             self.plan.append((np.asarray(union, dtype=np.int32), waves))
-        self.load_stream = torch.cuda.Stream()
-        self.infer_stream = torch.cuda.Stream()
-        self.copy_stream = torch.cuda.Stream()
+        # The device has few hardware queues per process; streams created later can share one, and
+        # then an event wait in one stream holds back the other.  A caller that builds several
+        # proxies passes the same three streams to all of them.
+        self.load_stream, self.infer_stream, self.copy_stream = streams or (
+            torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
 
     def run_pass(self, layer_done_events=None, single_stream=False, ffn_delay_cycles=0):
         """Issue one pass over all layers.  single_stream=True puts everything on the
@@ -198,7 +220,7 @@ class StreamingProxy:
         p, n_layers = self.pool, self.cfg.n_layers
         ls = self.infer_stream if single_stream else self.load_stream
         cs = self.infer_stream if single_stream else self.copy_stream
-        host = self.cfg.host_fraction > 0
+        host = bool(p.host_blobs)
         if host:
             p.prefetch_host(0, self.plan[0][0], cs)
             if n_layers > 1:

@@ -95,3 +95,25 @@ def test_layer_stage_comes_first():
     assert p.reclaim() == [(3, 1, op.DOWN)]
     assert p.restore() == [(3, 1, op.DOWN)]
     assert p.restore() == [("layer", 0)] and 0 in p.uncompressed
+
+
+def test_balanced_split_formula_bound_and_mixtral_case():
+    """Sec. 4.2: x_bw = beta_cpu / (beta_gpu + beta_cpu); ceil(3 L_r x_bw) down tensors;
+    0 <= x_i - x_bw < 1 / (3 L_r).  Exp#3's caption: Mixtral keeps 87.5 % on the compressed GPU
+    backend, i.e. a CPU share of 1/8, which is 3 whole down tensors of a rank holding 8
+    experts' shards and leaves 1.233 GB of the 1.409 GB per-GPU layer to decode."""
+    x, n_down, n_fused, xr = op.balanced_split(7.0, 1.0, 8)
+    assert x == 0.125 and (n_down, n_fused) == (3, 0) and xr == 0.125
+    per_gpu = 8 * 3 * 4096 * 14336 * 2 / 2
+    assert (1 - xr) * per_gpu / 1e9 == pytest.approx(1.233, abs=1e-3)
+    import random
+    rnd = random.Random(7)
+    for _ in range(2000):
+        bg, bc, L_r = rnd.uniform(50, 5000), rnd.uniform(1, 100), rnd.randint(1, 512)
+        x, n_down, n_fused, xr = op.balanced_split(bg, bc, L_r)
+        assert x * (bg + bc) == pytest.approx(bc)             # equal backend times: x / bc = (1 - x) / bg
+        assert x / bc == pytest.approx((1 - x) / bg)
+        if x < 1 / 3:
+            assert n_fused == 0 and -1e-12 <= xr - x < 1 / (3 * L_r)
+    assert op.balanced_split(100.0, 0.0, 16)[1:3] == (0, 0)
+    assert op.balanced_split(1.0, 1.0, 4)[1:3] == (4, 1)      # x = 1/2: 6 units = 4 down + 1 fused

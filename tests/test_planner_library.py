@@ -138,3 +138,18 @@ def test_argument_errors():
             B.fluxmoe_planner_tick(p, 10, 5, 1.0, [1.0, float("nan")])
     finally:
         B.fluxmoe_planner_destroy(p)
+
+
+def test_balanced_split_matches_oracle():
+    rng = np.random.Generator(np.random.Philox(11))
+    cases = [(7.0, 1.0, 8), (100.0, 0.0, 16), (1.0, 1.0, 4), (2800.0, 84.5, 160), (400.0, 50.0, 20)]
+    cases += [(float(rng.uniform(50, 5000)), float(rng.uniform(0, 3000)), int(rng.integers(1, 513)))
+              for _ in range(500)]
+    for bg, bc, L_r in cases:
+        x, nd, nf = B.fluxmoe_balanced_split(bg, bc, L_r)
+        xo, ndo, nfo, _ = op.balanced_split(bg, bc, L_r)
+        assert x == pytest.approx(xo, rel=1e-15) and (nd, nf) == (ndo, nfo), (bg, bc, L_r)
+    with pytest.raises(B.FluxmoeError):
+        B.fluxmoe_balanced_split(0.0, 1.0, 8)
+    with pytest.raises(B.FluxmoeError):
+        B.fluxmoe_balanced_split(1.0, 1.0, 0)
