@@ -337,6 +337,53 @@ int fluxmoe_planner_restore(fluxmoe_planner* p, fluxmoe_planner_move* moves, siz
 int fluxmoe_planner_state(const fluxmoe_planner* p, uint8_t* layer_pageable, uint8_t* on_host);
 
 /*
+ * PagedTensor on the device's virtual memory management (Sec. 4.1).  For tensor type d the
+ * layer group is A_d = L sigma_d bytes, padded to S_d = alignUp(A_d, g) for the allocation
+ * granularity g; a virtual range of N S_d bytes at v0_d is reserved and the type-d tensor of
+ * expert e in layer i (both 0-based here) has the stable address
+ *     v0_d + i S_d + e sigma_d.
+ * A pageable layer's range is mapped onto reusable block F_{i mod 2} (all pageable layers of one
+ * parity share one physical block), an uncompressed-resident layer's range onto a dedicated
+ * block.  Physical memory is (|U| + 2) (S_1 + S_2) bytes, of which
+ *     M_pad = (|U| + 2) sum_d (S_d - A_d)
+ * is padding.  Kernels read the tensors through these addresses with no translation of their
+ * own.  reusable_window[d] is one more view of the two reusable blocks, F_0 at +0 and F_1 at
+ * +S_d: when S_d = A_d for both types it can be bound as the slot arenas of a context with
+ * n_slots = 2 L (fluxmoe_bind_arenas), and materializing expert e of layer i into slot
+ * (i mod 2) L + e then fills exactly the bytes that layer i's own addresses show.
+ */
+typedef struct fluxmoe_paged_tensor fluxmoe_paged_tensor;
+
+typedef struct {
+    uint64_t granularity;          /* g */
+    uint64_t A[2], S[2];           /* [0] type 1, [1] type 2 */
+    uint64_t v0[2];                /* device virtual addresses (0 from fluxmoe_paged_tensor_layout) */
+    uint64_t reusable_window[2];   /* device virtual addresses (0 from fluxmoe_paged_tensor_layout) */
+    uint64_t virtual_bytes;        /* N (S_1 + S_2) */
+    uint64_t physical_bytes;       /* (|U| + 2) (S_1 + S_2) */
+    uint64_t pad_bytes;            /* M_pad */
+    uint32_t n_uncompressed, n_pageable;
+} fluxmoe_paged_tensor_info;
+
+/* The arithmetic alone (host, no device needed): sizes for a granularity and |U|. */
+int fluxmoe_paged_tensor_layout(const fluxmoe_desc* desc, uint64_t granularity,
+                                uint32_t n_uncompressed, fluxmoe_paged_tensor_info* out);
+/* Reserve, create and map on the current device (only n_layers, n_experts, hidden, ffn of desc
+ * are used).  uncompressed: host, n_layers flags, or NULL for all pageable.  Block contents are
+ * undefined until written.  EHIP if the device lacks virtual memory management. */
+int fluxmoe_paged_tensor_create(const fluxmoe_desc* desc, const uint8_t* uncompressed,
+                                fluxmoe_paged_tensor** out);
+/* Unmaps and frees everything; no kernel may still be using the addresses. */
+int fluxmoe_paged_tensor_destroy(fluxmoe_paged_tensor* p);
+int fluxmoe_paged_tensor_info_get(const fluxmoe_paged_tensor* p, fluxmoe_paged_tensor_info* out);
+int fluxmoe_paged_tensor_address(const fluxmoe_paged_tensor* p, uint32_t layer, int type,
+                                 uint32_t expert, void** out);
+/* Residency change of one layer (Sec. 4.1: "Only residency changes alter mappings"): remap its
+ * ranges to a new dedicated block (contents undefined) or back to its reusable block (the
+ * dedicated block is released).  Synchronises the device first; addresses do not change. */
+int fluxmoe_paged_tensor_set_class(fluxmoe_paged_tensor* p, uint32_t layer, int uncompressed);
+
+/*
  * Bandwidth-balanced tier split (Sec. 4.2 "Memory hierarchy model").  With the two backends
  * materializing their shares of a layer concurrently at effective rates beta_gpu and beta_cpu
  * (any one unit, in dense BF16 bytes per time), both finish together when the host share is

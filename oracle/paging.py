@@ -69,3 +69,27 @@ def waves(union_ids, n_avail: int):
     """Cut a sorted routed union into consecutive waves of at most n_avail experts."""
     ids = sorted(int(e) for e in union_ids)
     return [ids[i:i + n_avail] for i in range(0, len(ids), n_avail)]
+
+
+def paged_tensor_layout(N: int, L_r: int, hidden: int, ffn: int, g: int, n_uncompressed: int = 0):
+    """Sec. 4.1 "Formal model" and "alignment analysis": for d = 1 (fused gate/up) and d = 2
+    (down): sigma_d, A_d = L_r sigma_d, S_d = g ceil(A_d / g); virtual N S_d; physical blocks
+    |U| + 2 per type; M_pad = (|U| + 2) sum_d (S_d - A_d)."""
+    sigma = {2: hidden * ffn * 2}
+    sigma[1] = 2 * sigma[2]
+    A = {d: L_r * sigma[d] for d in (1, 2)}
+    S = {d: g * -(-A[d] // g) for d in (1, 2)}
+    return {"sigma": sigma, "A": A, "S": S,
+            "virtual": N * (S[1] + S[2]),
+            "physical": (n_uncompressed + 2) * (S[1] + S[2]),
+            "M_pad": (n_uncompressed + 2) * ((S[1] - A[1]) + (S[2] - A[2]))}
+
+
+def paged_tensor_address(v0: int, S: int, sigma: int, i: int, l: int) -> int:
+    """addr = v0 + (i - 1) S + (l - 1) sigma with the paper's 1-based layer i and expert l."""
+    return v0 + (i - 1) * S + (l - 1) * sigma
+
+
+def reusable_block_of(i: int) -> int:
+    """b_i = (i - 1) mod 2 for the paper's 1-based layer index."""
+    return (i - 1) % 2

@@ -58,6 +58,13 @@ class PlannerDecision(C.Structure):
                 ("tau_eff", C.c_double), ("tau_load", C.c_double)]
 
 
+class PagedTensorInfo(C.Structure):
+    _fields_ = [("granularity", C.c_uint64), ("A", C.c_uint64 * 2), ("S", C.c_uint64 * 2),
+                ("v0", C.c_uint64 * 2), ("reusable_window", C.c_uint64 * 2),
+                ("virtual_bytes", C.c_uint64), ("physical_bytes", C.c_uint64),
+                ("pad_bytes", C.c_uint64), ("n_uncompressed", C.c_uint32), ("n_pageable", C.c_uint32)]
+
+
 PLAN_KEEP, PLAN_RECLAIM, PLAN_RESTORE, PLAN_SKIP, PLAN_DONE = 0, 1, -1, 2, 3
 
 EXPORTS = {
@@ -94,6 +101,14 @@ EXPORTS = {
     "fluxmoe_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "fluxmoe_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]),
     "fluxmoe_device_errors": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
+    "fluxmoe_paged_tensor_layout": (C.c_int, [C.POINTER(Desc), C.c_uint64, C.c_uint32,
+                                              C.POINTER(PagedTensorInfo)]),
+    "fluxmoe_paged_tensor_create": (C.c_int, [C.POINTER(Desc), C.c_void_p, C.POINTER(C.c_void_p)]),
+    "fluxmoe_paged_tensor_destroy": (C.c_int, [C.c_void_p]),
+    "fluxmoe_paged_tensor_info_get": (C.c_int, [C.c_void_p, C.POINTER(PagedTensorInfo)]),
+    "fluxmoe_paged_tensor_address": (C.c_int, [C.c_void_p, C.c_uint32, C.c_int, C.c_uint32,
+                                               C.POINTER(C.c_void_p)]),
+    "fluxmoe_paged_tensor_set_class": (C.c_int, [C.c_void_p, C.c_uint32, C.c_int]),
     "fluxmoe_balanced_split": (C.c_int, [C.c_double, C.c_double, C.c_uint32, C.POINTER(C.c_double),
                                          C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]),
     "fluxmoe_planner_create": (C.c_int, [C.POINTER(PlannerDesc), C.c_void_p, C.POINTER(C.c_void_p)]),
@@ -331,3 +346,46 @@ def fluxmoe_balanced_split(beta_gpu, beta_cpu, experts_per_rank):
     _check(lib().fluxmoe_balanced_split(beta_gpu, beta_cpu, experts_per_rank, C.byref(x), C.byref(nd),
                                         C.byref(nf)))
     return float(x.value), int(nd.value), int(nf.value)
+
+
+# ---------------------------------------------------------------------- PagedTensor (VMM)
+def _desc(n_layers, n_experts, hidden, ffn):
+    return Desc(n_layers, n_experts, hidden, ffn, 4096, 12, 2 * n_experts, 0)
+
+
+def fluxmoe_paged_tensor_layout(n_layers, n_experts, hidden, ffn, granularity, n_uncompressed=0):
+    d, info = _desc(n_layers, n_experts, hidden, ffn), PagedTensorInfo()
+    _check(lib().fluxmoe_paged_tensor_layout(C.byref(d), granularity, n_uncompressed, C.byref(info)))
+    return info
+
+
+def fluxmoe_paged_tensor_create(n_layers, n_experts, hidden, ffn, uncompressed=None):
+    d, h = _desc(n_layers, n_experts, hidden, ffn), C.c_void_p()
+    flags = None
+    if uncompressed is not None:
+        flags = np.ascontiguousarray(uncompressed, dtype=np.uint8)
+        if flags.size != n_layers:
+            raise ValueError("uncompressed must have n_layers entries")
+    _check(lib().fluxmoe_paged_tensor_create(C.byref(d), None if flags is None else flags.ctypes.data,
+                                             C.byref(h)))
+    return h
+
+
+def fluxmoe_paged_tensor_destroy(p):
+    _check(lib().fluxmoe_paged_tensor_destroy(p))
+
+
+def fluxmoe_paged_tensor_info_get(p) -> PagedTensorInfo:
+    info = PagedTensorInfo()
+    _check(lib().fluxmoe_paged_tensor_info_get(p, C.byref(info)))
+    return info
+
+
+def fluxmoe_paged_tensor_address(p, layer, type_, expert) -> int:
+    out = C.c_void_p()
+    _check(lib().fluxmoe_paged_tensor_address(p, layer, type_, expert, C.byref(out)))
+    return int(out.value)
+
+
+def fluxmoe_paged_tensor_set_class(p, layer, uncompressed: bool):
+    _check(lib().fluxmoe_paged_tensor_set_class(p, layer, int(uncompressed)))
