@@ -20,6 +20,8 @@
 // and every weight byte is read exactly once per row tile.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace fluxmoe {
@@ -443,18 +445,17 @@ __global__ __launch_bounds__(512) void gemm_tiled_kernel(FfnArgs a) {
     u32x4 ga[4];
     u32x2 gb[8];
     const uint32_t n_steps = K / kTK;
-    auto gload = [&](uint32_t k0) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) ga[i] = *reinterpret_cast<const u32x4*>(a_src[i] + k0);
-#pragma unroll
-        for (int r = 0; r < 8; ++r) gb[r] = *reinterpret_cast<const u32x2*>(b_src + size_t(k0 + bk + r) * N);
+    // item n of a step's 12 global loads: 0..3 the lane's A rows, 4..11 the 8 k rows of its B tile
+    auto gload_item = [&](uint32_t k0, int n) __attribute__((always_inline)) {
+        if (n < 4) ga[n] = *reinterpret_cast<const u32x4*>(a_src[n] + k0);
+        else gb[n - 4] = *reinterpret_cast<const u32x2*>(b_src + size_t(k0 + bk + (n - 4)) * N);
     };
-    auto lstore = [&](uint16_t* buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<u32x4*>(buf + a_dst + 64 * i * kLdsPitch) = ga[i];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
+    // item n of a step's 8 LDS writes: 0..3 A rows, 4..7 column c = n - 4 of the transposed B tile
+    auto lstore_item = [&](uint16_t* buf, int n) __attribute__((always_inline)) {
+        if (n < 4) {
+            *reinterpret_cast<u32x4*>(buf + a_dst + 64 * n * kLdsPitch) = ga[n];
+        } else {
+            const int c = n - 4;
             u32x4 v;
             const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
             v.x = __builtin_amdgcn_perm(gb[1][c >> 1], gb[0][c >> 1], sel);
@@ -464,35 +465,83 @@ __global__ __launch_bounds__(512) void gemm_tiled_kernel(FfnArgs a) {
             *reinterpret_cast<u32x4*>(buf + b_dst + c * b_dst_step * kLdsPitch) = v;
         }
     };
-    auto mma_ks = [&](const uint16_t* buf, int ks) __attribute__((always_inline)) {
-        bf16x8 fa[2], fb[4];
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            fa[i] = *reinterpret_cast<const bf16x8*>(buf + a_frag + 32 * i * kLdsPitch + ks * 16);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            fb[j] = *reinterpret_cast<const bf16x8*>(buf + b_frag[j] + ks * 16);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    bf16x8 fa[2][2], fb[2][4];
+    // item n of the 6 fragment reads of sub-step ks into register set `set`
+    auto lfrag_item = [&](const uint16_t* buf, int ks, int set, int n) __attribute__((always_inline)) {
+        if (n < 2) fa[set][n] = *reinterpret_cast<const bf16x8*>(buf + a_frag + 32 * n * kLdsPitch + ks * 16);
+        else fb[set][n - 2] = *reinterpret_cast<const bf16x8*>(buf + b_frag[n - 2] + ks * 16);
+    };
+    auto mfma_item = [&](int set, int n) __attribute__((always_inline)) {
+        const int i = n >> 2, j = n & 3;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
     };
 
-    gload(0);
-    lstore(lds);
-    if (n_steps > 1) gload(kTK);
+    // One k step.  STORE: refill the other buffer from the staging registers; LOAD: fetch step
+    // s + 2 into them; NEXT: read the first fragments of the other buffer after the barrier.
+    // A workgroup moves 64 KB per step through the vector memory path (64 B/clk per CU) and again
+    // into LDS; issued in one burst, those instructions hold the issuing wavefronts for over a
+    // thousand cycles while the matrix cores idle.  They are therefore issued one at a time
+    // between the MFMAs (the scheduling barriers keep that order): the fragments of sub-step
+    // ks + 1 and the 8 LDS writes during sub-step 0, the 12 global loads during sub-steps 1 and 2.
+    // The step's barrier sits before the MFMAs of sub-step 3, which cover the first fragment
+    // reads from the other buffer.
+    auto step = [&](const uint16_t* cur, uint16_t* nxt, uint32_t k_next, auto STORE, auto LOAD, auto NEXT) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {                         // sub-step 0 (set 0)
+            mfma_item(0, n);
+            if (n < 6) lfrag_item(cur, 1, 1, n);
+            if (STORE.value) lstore_item(nxt, n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {                         // sub-step 1 (set 1)
+            mfma_item(1, n);
+            if (n < 6) lfrag_item(cur, 2, 0, n);
+            if (LOAD.value && n >= 2) gload_item(k_next, n - 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {                         // sub-step 2 (set 0)
+            mfma_item(0, n);
+            if (n < 6) lfrag_item(cur, 3, 1, n);
+            if (LOAD.value && n >= 2) gload_item(k_next, 6 + n - 2);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();                       // all reads of cur are in registers, nxt is complete
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {                         // sub-step 3 (set 1)
+            mfma_item(1, n);
+            if (NEXT.value && n < 6) lfrag_item(nxt, 0, 0, n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using Yes = std::integral_constant<bool, true>;
+    using No = std::integral_constant<bool, false>;
+
+#pragma unroll
+    for (int n = 0; n < 12; ++n) gload_item(0, n);
+#pragma unroll
+    for (int n = 0; n < 8; ++n) lstore_item(lds, n);
+    if (n_steps > 1) {
+#pragma unroll
+        for (int n = 0; n < 12; ++n) gload_item(kTK, n);
+    }
     __syncthreads();
-    for (uint32_t s = 0; s < n_steps; ++s) {
-        uint16_t* cur = lds + (s & 1) * (2 * kTile);
-        uint16_t* nxt = lds + ((s + 1) & 1) * (2 * kTile);
-        mma_ks(cur, 0);
-        if (s + 1 < n_steps) lstore(nxt);
-        if (s + 2 < n_steps) gload((s + 2) * kTK);
-        mma_ks(cur, 1);
-        mma_ks(cur, 2);
-        mma_ks(cur, 3);
-        __syncthreads();
+#pragma unroll
+    for (int n = 0; n < 6; ++n) lfrag_item(lds, 0, 0, n);
+    {
+        uint16_t* cur = lds;
+        uint16_t* nxt = lds + 2 * kTile;
+        uint32_t s = 0;
+        for (; s + 2 < n_steps; ++s) {
+            step(cur, nxt, (s + 2) * kTK, Yes{}, Yes{}, Yes{});
+            uint16_t* tmp = cur; cur = nxt; nxt = tmp;
+        }
+        if (s + 1 < n_steps) {
+            step(cur, nxt, 0, Yes{}, No{}, Yes{});
+            uint16_t* tmp = cur; cur = nxt; nxt = tmp;
+        }
+        step(cur, nxt, 0, No{}, No{}, No{});
     }
 
     // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4
@@ -504,6 +553,214 @@ __global__ __launch_bounds__(512) void gemm_tiled_kernel(FfnArgs a) {
             if (row >= t.rows) continue;
             if (MODE == 1) {
                 const uint32_t col = n_base + 4u * q + 2u * wn;      // two adjacent columns
+                if (col >= N) continue;
+                uint32_t packed = 0;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const float ga_ = acc[i][j][r];
+                    const float up = acc[i][j + 2][r];
+                    const float h = ga_ / (1.0f + __expf(-ga_)) * up;
+                    packed |= f32_to_bf16_rne(h) << (16 * j);
+                }
+                *reinterpret_cast<uint32_t*>(a.hbuf + size_t(t.row0 + row) * a.F + col) = packed;
+            } else {
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const uint32_t col = n_base + 4u * (32 * half + q) + 2u * wn;
+                    if (col >= N) continue;
+                    *reinterpret_cast<float2*>(a.ybuf + size_t(t.row0 + row) * a.H + col) =
+                        make_float2(acc[i][half][r], acc[i][half + 2][r]);
+                }
+            }
+        }
+}
+
+// The same tiling with four wavefronts, one per SIMD, each owning 128 x 128 (4 x 4 MFMA tiles, 256
+// accumulator registers).  LDS fragment traffic per flop falls by a third against the 64 x 128
+// wavefront tile (a 128 x 128 tile reads 256 fragment rows per k for 16384 multiply-adds, the
+// 64 x 128 one 192 for 8192), which is what bounds the eight-wavefront kernel.  With a single
+// wavefront per SIMD nothing hides a wait, so the loop is software pipelined inside the
+// wavefront: the fragments of sub-step ks + 1 are read while sub-step ks is multiplied, the
+// refill of the other LDS buffer and the global loads of step s + 2 are spread over the MFMAs of
+// sub-steps 0 and 1, and the step's only barrier sits before the MFMAs of sub-step 3, which then
+// cover the first fragment reads from the other buffer.
+template <int MODE>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void gemm_tiled4_kernel(FfnArgs a) {
+    extern __shared__ __align__(16) uint16_t lds[];
+    const uint32_t K = MODE == 1 ? a.H : a.F;
+    const uint32_t N = MODE == 1 ? a.F : a.H;
+    const uint32_t ncols_tile = MODE == 1 ? 128u : 256u;
+    const uint32_t n_ct = (N + ncols_tile - 1) / ncols_tile;
+    const uint32_t n_rt = uint32_t(a.n_tiles[0]);
+    const uint32_t n_sn = (n_ct + kSuperN - 1) / kSuperN;
+    const uint32_t xcd = blockIdx.x % 8u, jj = blockIdx.x / 8u;
+    const uint32_t st = (jj / (kSuperM * kSuperN)) * 8u + xcd;
+    const uint32_t within = jj % (kSuperM * kSuperN);
+    const uint32_t row_tile = (st / n_sn) * kSuperM + within / kSuperN;
+    const uint32_t col_tile = (st % n_sn) * kSuperN + within % kSuperN;
+    if (row_tile >= n_rt || col_tile >= n_ct) return;
+    TileInfo t;
+    if (!tile_info(a, row_tile, t)) return;
+    const uint32_t n_base = col_tile * ncols_tile;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int q = lane & 31;
+    constexpr int kTile = kTM * kLdsPitch;
+
+    // global -> register staging.  A: 8 lanes cover one row's 64 k; rows tid / 8 + 32 i.
+    const uint16_t* a_base = MODE == 1 ? a.tokens : a.hbuf;
+    uint32_t a_off[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int32_t r = min(int32_t(tid >> 3) + 32 * i, t.rows - 1);
+        if (MODE == 1) {
+            const int32_t pr = a.sorted_pair[t.row0 + r];
+            a_off[i] = (uint32_t(pr) / a.K) * a.H + 8 * (tid & 7);
+        } else {
+            a_off[i] = uint32_t(t.row0 + r) * a.F + 8 * (tid & 7);
+        }
+    }
+    const int a_dst = (tid >> 3) * kLdsPitch + 8 * (tid & 7);          // + 32 i rows
+    // B: two lane tiles of 4 consecutive columns x 8 k rows: k = 8 (tid / 64) + 32 u
+    const uint32_t cg = tid & 63;
+    const uint32_t bk = 8u * (tid >> 6);
+    const uint16_t* b_src;
+    int b_dst_row;
+    {
+        const size_t mat = size_t(a.H) * a.F;
+        if (MODE == 1) {
+            const uint32_t col = min(n_base + 4u * (cg & 31u), N - 4);
+            b_src = a.slots13 + size_t(t.slot) * 2 * mat + (cg >= 32 ? mat : 0) + col;
+            b_dst_row = int(cg >> 5) * 128 + int(cg & 31);
+        } else {
+            const uint32_t col = min(n_base + 4u * cg, N - 4);
+            b_src = a.slots2 + size_t(t.slot) * mat + col;
+            b_dst_row = int(cg);
+        }
+    }
+    constexpr int b_dst_step = MODE == 1 ? 32 : 64;
+    const int b_dst = kTile + b_dst_row * kLdsPitch + int(bk);
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int kfrag = 8 * (lane >> 5);
+    const int a_frag = (wm * 128 + q) * kLdsPitch + kfrag;              // + 32 i rows
+    // B tile j of this wavefront: MODE 2 rows 32 (4 wn + j) + q; MODE 1 rows 128 (j / 2) + 32 (2 wn + j % 2) + q
+    const int b_frag = kTile + (MODE == 1 ? (2 * wn * 32 + q) : (4 * wn * 32 + q)) * kLdsPitch + kfrag;
+    auto b_frag_off = [](int j) { return (MODE == 1 ? ((j >> 1) * 128 + (j & 1) * 32) : (j * 32)) * kLdsPitch; };
+
+    u32x4 ga[8];
+    u32x2 gb[2][8];
+    const uint32_t n_steps = K / kTK;
+    // item n of a step's 24 global loads: 0..7 the lane's A rows, 8..23 the 2 x 8 k rows of its B tiles
+    auto gload_item = [&](uint32_t k0, int n) __attribute__((always_inline)) {
+        if (n < 8) ga[n] = *reinterpret_cast<const u32x4*>(a_base + a_off[n] + k0);
+        else gb[(n - 8) >> 3][(n - 8) & 7] =
+                 *reinterpret_cast<const u32x2*>(b_src + size_t(k0 + bk + 32 * ((n - 8) >> 3) + ((n - 8) & 7)) * N);
+    };
+    // item n of a step's 16 LDS writes: 0..7 A rows, 8..15 column c of transposed B tile u
+    auto lstore_item = [&](uint16_t* buf, int n) __attribute__((always_inline)) {
+        if (n < 8) {
+            *reinterpret_cast<u32x4*>(buf + a_dst + 32 * n * kLdsPitch) = ga[n];
+        } else {
+            const int u = (n - 8) >> 2, c = (n - 8) & 3;
+            u32x4 v;
+            const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+            v.x = __builtin_amdgcn_perm(gb[u][1][c >> 1], gb[u][0][c >> 1], sel);
+            v.y = __builtin_amdgcn_perm(gb[u][3][c >> 1], gb[u][2][c >> 1], sel);
+            v.z = __builtin_amdgcn_perm(gb[u][5][c >> 1], gb[u][4][c >> 1], sel);
+            v.w = __builtin_amdgcn_perm(gb[u][7][c >> 1], gb[u][6][c >> 1], sel);
+            *reinterpret_cast<u32x4*>(buf + b_dst + 32 * u + c * b_dst_step * kLdsPitch) = v;
+        }
+    };
+    bf16x8 fa[2][4], fb[2][4];
+    // item n of the 8 fragment reads of sub-step ks into register set `set`
+    auto lfrag_item = [&](const uint16_t* buf, int ks, int set, int n) __attribute__((always_inline)) {
+        if (n < 4) fa[set][n] = *reinterpret_cast<const bf16x8*>(buf + a_frag + 32 * n * kLdsPitch + ks * 16);
+        else fb[set][n - 4] = *reinterpret_cast<const bf16x8*>(buf + b_frag + b_frag_off(n - 4) + ks * 16);
+    };
+    auto mfma_item = [&](int set, int n) __attribute__((always_inline)) {
+        const int i = n >> 2, j = n & 3;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+    };
+
+    // One k step.  STORE: refill the other buffer from the staging registers; LOAD: fetch step
+    // s + 2 into them; NEXT: read the first fragments of the other buffer after the barrier.
+    // Every memory instruction is issued between two MFMAs (the scheduling barriers keep that
+    // order): the fragments of sub-step ks + 1 during sub-step ks, the 16 LDS writes during
+    // sub-step 0, the 24 global loads during sub-steps 1 and 2.
+    auto step = [&](const uint16_t* cur, uint16_t* nxt, uint32_t k_next, auto STORE, auto LOAD, auto NEXT) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {                        // sub-step 0 (set 0)
+            mfma_item(0, n);
+            if (n < 8) lfrag_item(cur, 1, 1, n);
+            if (STORE.value) lstore_item(nxt, n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {                        // sub-step 1 (set 1)
+            mfma_item(1, n);
+            if (n < 8) lfrag_item(cur, 2, 0, n);
+            if (LOAD.value && n >= 4) gload_item(k_next, n - 4);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {                        // sub-step 2 (set 0)
+            mfma_item(0, n);
+            if (n < 8) lfrag_item(cur, 3, 1, n);
+            if (LOAD.value && n >= 4) gload_item(k_next, 12 + n - 4);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();                       // all reads of cur are in registers, nxt is complete
+#pragma unroll
+        for (int n = 0; n < 16; ++n) {                        // sub-step 3 (set 1)
+            mfma_item(1, n);
+            if (NEXT.value && n < 8) lfrag_item(nxt, 0, 0, n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    using Yes = std::integral_constant<bool, true>;
+    using No = std::integral_constant<bool, false>;
+
+#pragma unroll
+    for (int n = 0; n < 24; ++n) gload_item(0, n);
+#pragma unroll
+    for (int n = 0; n < 16; ++n) lstore_item(lds, n);
+    if (n_steps > 1) {
+#pragma unroll
+        for (int n = 0; n < 24; ++n) gload_item(kTK, n);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int n = 0; n < 8; ++n) lfrag_item(lds, 0, 0, n);
+    uint16_t* cur = lds;
+    uint16_t* nxt = lds + 2 * kTile;
+    uint32_t s = 0;
+    for (; s + 2 < n_steps; ++s) {
+        step(cur, nxt, (s + 2) * kTK, Yes{}, Yes{}, Yes{});
+        uint16_t* tmp = cur; cur = nxt; nxt = tmp;
+    }
+    if (s + 1 < n_steps) {
+        step(cur, nxt, 0, Yes{}, No{}, Yes{});
+        uint16_t* tmp = cur; cur = nxt; nxt = tmp;
+    }
+    step(cur, nxt, 0, No{}, No{}, No{});
+
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int32_t row = wm * 128 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            if (row >= t.rows) continue;
+            if (MODE == 1) {
+                const uint32_t col = n_base + 4u * q + 2u * wn;
                 if (col >= N) continue;
                 uint32_t packed = 0;
 #pragma unroll
@@ -565,12 +822,19 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
     const dim3 g2((strips2 + 3) / 4, a.tiles_cap, a.ksplit);
     if (a.m_tile == 256) {
         const size_t lds_bytes = 4 * size_t(kTM) * kLdsPitch * sizeof(uint16_t);
+        const bool four = a.tiled_waves == 4;
         static bool attr_set = false;
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<1>),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
             if (e != hipSuccess) return e;
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<2>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled4_kernel<1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled4_kernel<2>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
             if (e != hipSuccess) return e;
             attr_set = true;
@@ -581,10 +845,12 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
             const uint32_t supers = (n_sm * n_sn + 7) / 8 * 8;      // whole rounds over the 8 XCDs
             return dim3(supers * kSuperM * kSuperN, 1, 1);
         };
-        hipLaunchKernelGGL(gemm_tiled_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), lds_bytes, stream, a);
+        if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<1>, grid_for((a.F + 127) / 128), dim3(256), lds_bytes, stream, a);
+        else hipLaunchKernelGGL(gemm_tiled_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), lds_bytes, stream, a);
         mark(2, 0);
         mark(3, 1);
-        hipLaunchKernelGGL(gemm_tiled_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), lds_bytes, stream, a);
+        if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<2>, grid_for((a.H + 255) / 256), dim3(256), lds_bytes, stream, a);
+        else hipLaunchKernelGGL(gemm_tiled_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), lds_bytes, stream, a);
         mark(3, 0);
         const dim3 gc2((a.H / 4 + 255) / 256, a.T, 1);
         mark(4, 1);

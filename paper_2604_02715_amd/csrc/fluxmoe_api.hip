@@ -98,6 +98,7 @@ struct fluxmoe_ctx {
     int tune_waves = 16;
     int tune_wg_per_cu = 8;
     int tune_chunk = 1;
+    int tune_tiled_waves = 8;             // FLUXMOE_FFN_TILED_WAVES: 8 (64 x 128 per wavefront) or 4 (128 x 128)
     // optional kernel timing (fluxmoe_profile_*)
     bool profiling = false;
     struct Span { hipEvent_t a, b; int kind; };
@@ -271,6 +272,10 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     if (const char* v = std::getenv("FLUXMOE_DECODE_WG_PER_CU")) {
         const int w = std::atoi(v);
         if (w >= 1 && w <= 64) c->tune_wg_per_cu = w;
+    }
+    if (const char* v = std::getenv("FLUXMOE_FFN_TILED_WAVES")) {
+        const int w = std::atoi(v);
+        if (w == 4 || w == 8) c->tune_tiled_waves = w;
     }
     *out_ctx = c;
     g_err[0] = 0;
@@ -868,6 +873,7 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, u
     a.ybuf = reinterpret_cast<float*>(w + p.off_y);
     a.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
     a.pairs_cap = p.pairs_cap; a.tiles_cap = p.tiles_cap; a.m_tile = p.m_tile; a.ksplit = p.ksplit;
+    a.tiled_waves = c->tune_tiled_waves;
 
     if (c->load_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_load[layer], 0));
     HIPCHECK(launch_ffn(a, c->n_cus, stream, c->profiling ? ffn_span_hook : nullptr, c));
@@ -928,6 +934,7 @@ int fluxmoe_shared_expert_ffn(fluxmoe_ctx* c, const uint16_t* w13, const uint16_
     a.ybuf = reinterpret_cast<float*>(w + p.off_y);
     a.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
     a.pairs_cap = p.pairs_cap; a.tiles_cap = p.tiles_cap; a.m_tile = p.m_tile; a.ksplit = p.ksplit;
+    a.tiled_waves = c->tune_tiled_waves;
     HIPCHECK(launch_ffn(a, c->n_cus, stream, c->profiling ? ffn_span_hook : nullptr, c));
     return FLUXMOE_OK;
 }
