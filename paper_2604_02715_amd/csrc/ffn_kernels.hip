@@ -130,6 +130,8 @@ __device__ __forceinline__ uint32_t comp(const uint4& v, int i) {
 
 // k chunks per wavefront held in the register ring (one being multiplied, the rest in flight)
 template <int MI> struct RingDepth { static constexpr int value = MI >= 4 ? 3 : 4; };
+// the smaller body a kernel for tiles of 16 MI rows also carries (for tiles with few rows)
+template <int MI> struct SmallerBody { static constexpr int value = MI == 6 ? 4 : (MI >= 2 ? MI / 2 : 1); };
 
 // One wavefront's product C[16*MI rows][128 columns] = A[rows][k range] * B[k range][strip].
 template <int MI>
@@ -190,7 +192,19 @@ struct StripGemm {
 #pragma unroll
         for (int s = 0; s < kStages - 1; ++s)
             if (uint32_t(s) < n) load(st[s], arow, bcol, ldb, kb + s * kChunk);
-        for (uint32_t base = 0; base < n; base += kStages) {
+        // Steady state without branches: a conditional load inside the loop makes the compiler
+        // wait for the newest loads at the join (it must assume the path that issued none), which
+        // serialises the ring.  Rounds in which every load is in range run unconditionally; the
+        // last rounds take the guarded form.
+        uint32_t base = 0;
+        for (; base + 2 * kStages - 2 < n; base += kStages) {
+#pragma unroll
+            for (int s = 0; s < kStages; ++s) {
+                load(st[(s + kStages - 1) % kStages], arow, bcol, ldb, kb + (base + s + kStages - 1) * kChunk);
+                mma(st[s]);
+            }
+        }
+        for (; base < n; base += kStages) {
 #pragma unroll
             for (int s = 0; s < kStages; ++s) {
                 const uint32_t i = base + s;
@@ -241,10 +255,7 @@ __device__ __forceinline__ bool tile_info(const FfnArgs& a, uint32_t tile, TileI
 // SwiGLU and stores.  Splitting the two matrices over two wavefronts halves the accumulator
 // registers per wavefront, which is what leaves room for the deep load ring.
 template <int MI>
-__global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
-    __shared__ float xch[2][MI * 8 * 4][64];     // [pair][mi, c, r][lane]
-    TileInfo t;
-    if (!tile_info(a, blockIdx.y, t)) return;     // uniform over the workgroup
+__device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileInfo& t, float (*xch)[64]) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int pair = wave >> 1;
@@ -273,7 +284,7 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
 #pragma unroll
             for (int c = 0; c < 8; ++c)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) xch[pair][(mi * 8 + c) * 4 + r][lane] = g.acc[mi][c][r];
+                for (int r = 0; r < 4; ++r) xch[pair * (MI * 32) + (mi * 8 + c) * 4 + r][lane] = g.acc[mi][c][r];
     }
     __syncthreads();
     if (mat_id == 1 || !col_ok) return;
@@ -287,7 +298,7 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 const float ga = g.acc[mi][c][r];
-                const float up = xch[pair][(mi * 8 + c) * 4 + r][lane];
+                const float up = xch[pair * (MI * 32) + (mi * 8 + c) * 4 + r][lane];
                 const float h = ga / (1.0f + __expf(-ga)) * up;
                 hb[c] = f32_to_bf16_rne(h);
             }
@@ -300,11 +311,22 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
         }
 }
 
+// Row tiles hold up to 16 MI rows, sized with headroom over the mean rows per expert so that an
+// expert's weights are streamed once; tiles with few rows take a body compiled for fewer 16-row
+// MFMA tiles (less work per chunk, same registers reserved).
+template <int MI>
+__global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
+    __shared__ float xch[2 * MI * 8 * 4][64];     // [pair][mi, c, r][lane]
+    TileInfo t;
+    if (!tile_info(a, blockIdx.y, t)) return;     // uniform over the workgroup
+    constexpr int kSmall = SmallerBody<MI>::value;
+    if (kSmall < MI && t.rows <= 16 * kSmall) gemm1_swiglu_body<kSmall>(a, t, xch);
+    else gemm1_swiglu_body<MI>(a, t, xch);
+}
+
 // y[split][row][n] = h[row][k range] W2[k range][n]
 template <int MI>
-__global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
-    TileInfo t;
-    if (!tile_info(a, blockIdx.y, t)) return;
+__device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const uint32_t strip = blockIdx.x * 4 + wave;
@@ -341,6 +363,15 @@ __global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
             dst[0] = lo;
             dst[1] = hi;
         }
+}
+
+template <int MI>
+__global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
+    TileInfo t;
+    if (!tile_info(a, blockIdx.y, t)) return;
+    constexpr int kSmall = SmallerBody<MI>::value;
+    if (kSmall < MI && t.rows <= 16 * kSmall) gemm2_body<kSmall>(a, t);
+    else gemm2_body<MI>(a, t);
 }
 
 // ------------------------------------------------------------------ large row tiles (MFMA bound)
@@ -858,16 +889,18 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
         mark(4, 0);
         return hipGetLastError();
     }
-    if (a.m_tile != 16 && a.m_tile != 32 && a.m_tile != 64) return hipErrorInvalidValue;
+    if (a.m_tile != 16 && a.m_tile != 32 && a.m_tile != 64 && a.m_tile != 96) return hipErrorInvalidValue;
     mark(2, 1);
     if (a.m_tile == 16) hipLaunchKernelGGL(gemm1_swiglu_kernel<1>, g1, dim3(256), 0, stream, a);
     else if (a.m_tile == 32) hipLaunchKernelGGL(gemm1_swiglu_kernel<2>, g1, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(gemm1_swiglu_kernel<4>, g1, dim3(256), 0, stream, a);
+    else if (a.m_tile == 64) hipLaunchKernelGGL(gemm1_swiglu_kernel<4>, g1, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(gemm1_swiglu_kernel<6>, g1, dim3(256), 0, stream, a);
     mark(2, 0);
     mark(3, 1);
     if (a.m_tile == 16) hipLaunchKernelGGL(gemm2_kernel<1>, g2, dim3(256), 0, stream, a);
     else if (a.m_tile == 32) hipLaunchKernelGGL(gemm2_kernel<2>, g2, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(gemm2_kernel<4>, g2, dim3(256), 0, stream, a);
+    else if (a.m_tile == 64) hipLaunchKernelGGL(gemm2_kernel<4>, g2, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(gemm2_kernel<6>, g2, dim3(256), 0, stream, a);
     mark(3, 0);
     const dim3 gc((a.H / 4 + 255) / 256, a.T, 1);
     mark(4, 1);

@@ -12,6 +12,7 @@
 #include <array>
 #include <atomic>
 #include <cstdlib>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <thread>
@@ -125,12 +126,17 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
     const uint64_t pairs = uint64_t(T) * K;
     const uint64_t groups = std::max<uint64_t>(1, std::min<uint64_t>(E, pairs));
     const uint64_t avg = (pairs + groups - 1) / groups;
-    p.m_tile = avg > 32 ? 64 : (avg > 16 ? 32 : 16);
-    // many rows per expert: the LDS-tiled MFMA kernels (they need k extents that are multiples of 64)
-    if (avg >= 192 && H % 64 == 0 && F % 64 == 0) p.m_tile = 256;
+    // Row tile: every extra tile of an expert streams that expert's weights again, so the tile
+    // is sized for the mean rows per expert plus four standard deviations of a Poisson count
+    // (the kernels run a half-size body for tiles that are at most half full).
+    const double want = double(avg) + 4.0 * std::sqrt(double(avg));
+    p.m_tile = want > 64 ? 96 : (want > 32 ? 64 : (want > 16 ? 32 : 16));
+    // more rows per expert than one 96-row tile: the LDS-tiled MFMA kernels, one pass over the
+    // weights for up to 256 rows (they need k extents that are multiples of 64)
+    if (want > 96 && H % 64 == 0 && F % 64 == 0) p.m_tile = 256;
     if (const char* v = std::getenv("FLUXMOE_FFN_MTILE")) {
         const int m = std::atoi(v);
-        if (m == 16 || m == 32 || m == 64 || (m == 256 && H % 64 == 0 && F % 64 == 0)) p.m_tile = uint32_t(m);
+        if (m == 16 || m == 32 || m == 64 || m == 96 || (m == 256 && H % 64 == 0 && F % 64 == 0)) p.m_tile = uint32_t(m);
     }
     p.pairs_cap = uint32_t(std::max<uint64_t>(pairs, 1));
     p.tiles_cap = uint32_t(pairs / p.m_tile + groups + 1);
