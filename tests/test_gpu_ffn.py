@@ -65,7 +65,11 @@ def test_c1_tiny():
     dict(tokens=1, top_k=1),                                   # a single pair
     dict(tokens=3, top_k=2, hidden=72, ffn=200),               # ragged strips and k tails
     dict(tokens=40, top_k=2, hidden=136, ffn=264, n_experts=4, n_slots=4),  # 8-column last strip
-    dict(tokens=200, top_k=2, n_experts=3, n_slots=3),         # several row tiles per expert
+    dict(tokens=200, top_k=2, n_experts=3, n_slots=3),         # 133 rows per expert: LDS-tiled path
+    dict(tokens=200, top_k=2, n_experts=3, n_slots=3, hidden=136, ffn=264),   # same rows, shapes the tiled path
+                                                               # cannot take: two 96-row tiles per expert
+    dict(tokens=256, top_k=2, hidden=320, ffn=448),            # about 64 rows per expert: 96-row tiles, both bodies
+    dict(tokens=120, top_k=2, routing="zipf"),                 # a popular expert overflows its 64-row tile
     dict(tokens=33, top_k=4, hidden=136, ffn=264, n_experts=5, n_slots=5),
     dict(tokens=16, top_k=8, hidden=256, ffn=4096),            # K split of the second product
     dict(tokens=700, top_k=2, n_experts=3, n_slots=3, hidden=192, ffn=320),   # LDS-tiled path, ragged edges
@@ -73,6 +77,16 @@ def test_c1_tiny():
 ])
 def test_shapes(kw):
     run_ffn_case(inputs.scaled(inputs.CONFIGS["c1_tiny"], **kw), seed=1)
+
+
+def test_four_wavefront_variant_of_the_tiled_kernels(monkeypatch):
+    """FLUXMOE_FFN_TILED_WAVES=4 selects the 128 x 128 per-wavefront variant; same results."""
+    kw = dict(tokens=700, top_k=2, n_experts=3, n_slots=3, hidden=192, ffn=320)
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], **kw)
+    eight = run_ffn_case(cfg, seed=1)
+    monkeypatch.setenv("FLUXMOE_FFN_TILED_WAVES", "4")
+    four = run_ffn_case(cfg, seed=1)
+    assert offn.rel_frobenius(four, eight) < 1e-5
 
 
 def test_wave_mode_accumulates_to_the_single_shot_result():
