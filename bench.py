@@ -52,6 +52,12 @@ def main():
     ap.add_argument("--exp3", action="store_true",
                     help="standalone decompression in the paper's Exp#3 setting: one GPU's rank-local "
                          "shard of one layer per run, latency mean/std/P99 over repetitions")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="context for the MFMA roofline: rate of a loop of independent BF16 MFMAs with no memory "
+                         "traffic, on constant and on random operands (the chip's clock depends on operand content)")
+    ap.add_argument("--vendor-gemm", action="store_true",
+                    help="with --ffn-rows-per-expert: also time torch.matmul (the vendor BLAS) on the two GEMM shapes "
+                         "with B stored [K][N] as the slots hold it (context, not part of the path)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic) and report their rate; "
                          "under rocprofv3 --pmc they calibrate FETCH_SIZE / WRITE_SIZE")
@@ -66,6 +72,8 @@ def main():
     from paper_2604_02715_amd import harness, inputs
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.mfma_probe:
+        return bench_mfma_probe(args)
     if args.exp3:
         return bench_exp3(args)
     cfg = inputs.CONFIGS[args.config]
@@ -267,6 +275,42 @@ def bench_exp3(args):
                       "vs_baseline": None, "higher_is_better": True, "rows": rows}), flush=True)
 
 
+def bench_mfma_probe(args):
+    """MFMA-only loop (fluxmoe_mfma_probe) on three operand contents."""
+    import numpy as np
+    import torch
+    from paper_2604_02715_amd import binding as B
+
+    n_wg, iters = torch.cuda.get_device_properties(0).multi_processor_count, 200000
+    out = torch.zeros(n_wg * 256, dtype=torch.float32, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(1)
+    contents = {
+        "constant": torch.full((32768,), 1.0, dtype=torch.bfloat16, device="cuda"),
+        "gaussian": torch.randn(32768, generator=g, device="cuda").to(torch.bfloat16),
+        "random_bits": (torch.randint(0, 1 << 16, (32768,), generator=g, device="cuda", dtype=torch.int32) & 0xBFFF
+                        ).to(torch.int16).view(torch.bfloat16),      # any sign/mantissa, exponent below 2^64
+    }
+    res = {}
+    for name, t in contents.items():
+        best = None
+        for _ in range(3):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            B.fluxmoe_mfma_probe(t.data_ptr(), out.data_ptr(), n_wg, iters, torch.cuda.current_stream().cuda_stream)
+            b.record()
+            torch.cuda.synchronize()
+            ms = a.elapsed_time(b)
+            best = ms if best is None else min(best, ms)
+        flops = n_wg * 4.0 * iters * 16 * 32768
+        res[name] = {"ms": round(best, 3), "TFLOPs": round(flops / (best * 1e-3) / 1e12, 1),
+                     "frac_of_peak": round(flops / (best * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)}
+    print(json.dumps({"metric": "mfma_only_loop", "unit": "TFLOP/s", "n_gpus": 1, "dtype": "bf16",
+                      "config": {"workload": "mfma_probe", "workgroups": n_wg, "iters": iters,
+                                 "mfma": "v_mfma_f32_32x32x16_bf16, 16 accumulators per wavefront, 4 wavefronts per CU"},
+                      "peak": MFMA_BF16_PEAK_TFLOPS, "operands": res}), flush=True)
+
+
 def bench_ffn_rows(cfg, args):
     """FFN only, M rows per expert on every expert of the layer (balanced synthetic routing):
     the MFMA-bound side of the expert GEMM.  Materialization runs once, untimed."""
@@ -314,6 +358,25 @@ def bench_ffn_rows(cfg, args):
         err = offn.rel_frobenius(out[torch.from_numpy(sel).cuda()].cpu().numpy(), want)
         assert err <= 1e-3, err
     tf = flops / (ms * 1e-3) / 1e12
+    vendor = None
+    if args.vendor_gemm:
+        # one [rows][K] x [K][N] product per GEMM shape with all T*K rows against one expert's matrix:
+        # the same flops as the grouped product
+        def mm(rows, kk, nn):
+            aa = torch.randn(rows, kk, device="cuda").to(torch.bfloat16)
+            bb = (torch.randn(kk, nn, device="cuda") * 0.02).to(torch.bfloat16)
+            for _ in range(3):
+                aa @ bb
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                aa @ bb
+            e1.record()
+            torch.cuda.synchronize()
+            return 2.0 * rows * kk * nn / (e0.elapsed_time(e1) / 10 * 1e-3) / 1e12
+        vendor = {"what": "torch.matmul bf16, B row-major [K][N], one product of all rows per GEMM shape",
+                  "gemm1_TFLOPs": round(mm(T * K, cfg.hidden, 2 * cfg.ffn), 1),
+                  "gemm2_TFLOPs": round(mm(T * K, cfg.ffn, cfg.hidden), 1)}
     print(json.dumps({
         "metric": "expert_ffn_throughput", "value": round(tf, 1), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
@@ -328,7 +391,8 @@ def bench_ffn_rows(cfg, args):
         "ffn": {"frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                 "gemm2_TFLOPs": round(2.0 * cfg.hidden * cfg.ffn * T * K / (g2 * 1e-3) / 1e12, 1),
                 "kernels_ms": {k: round(prof[k][0] / max(1, prof[k][1]), 4)
-                               for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")}}}), flush=True)
+                               for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")}},
+        "vendor_gemm": vendor}), flush=True)
     pool.close()
 
 

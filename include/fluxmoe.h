@@ -244,6 +244,16 @@ int fluxmoe_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_w
                         void* stream);
 
 /*
+ * Measurement aid: n_workgroups workgroups of four wavefronts each issue iters x 16 independent
+ * v_mfma_f32_32x32x16_bf16 (32768 flops each) on operands taken once from `operands` (device, 64 KiB
+ * of BF16 values, 16-byte aligned) and no memory traffic in the loop; `out` (device, n_workgroups *
+ * 256 floats) receives sums that keep the work alive.  Timed by the caller, it gives the rate the
+ * matrix cores sustain for that operand content (the chip's clock depends on it).  Needs no context.
+ */
+int fluxmoe_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, uint32_t iters,
+                       void* stream);
+
+/*
  * Kernel timing for benchmarks.  While enabled, every kernel the library launches is
  * bracketed by HIP events on its own stream.  fluxmoe_profile_collect waits for them, adds
  * the elapsed milliseconds and launch counts per kind and forgets them:

@@ -98,6 +98,7 @@ EXPORTS = {
     "fluxmoe_shared_expert_ffn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                             C.c_void_p, C.c_uint32, C.c_void_p]),
     "fluxmoe_stream_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]),
+    "fluxmoe_mfma_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p]),
     "fluxmoe_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "fluxmoe_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]),
     "fluxmoe_device_errors": (C.c_int, [C.c_void_p, C.POINTER(C.c_uint32)]),
@@ -254,6 +255,10 @@ def fluxmoe_shared_expert_ffn(ctx, w13_ptr, w2_ptr, tokens_ptr, T, out_ptr, flag
 
 def fluxmoe_stream_copy(dst_ptr, src_ptr, nbytes, n_workgroups, stream=None):
     _check(lib().fluxmoe_stream_copy(dst_ptr, src_ptr, nbytes, n_workgroups, stream))
+
+
+def fluxmoe_mfma_probe(operands_ptr, out_ptr, n_workgroups, iters, stream=None):
+    _check(lib().fluxmoe_mfma_probe(operands_ptr, out_ptr, n_workgroups, iters, stream))
 
 
 PROFILE_KINDS = ("decode", "grouping", "gemm1_swiglu", "gemm2", "combine")

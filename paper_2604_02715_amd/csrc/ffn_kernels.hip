@@ -837,7 +837,44 @@ __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
     *reinterpret_cast<float4*>(o) = s;
 }
 
+// Measurement aid: nothing but independent 32x32x16 BF16 MFMAs (16 accumulators per wavefront, one
+// wavefront per SIMD) on operands read once from `in`: what the matrix cores sustain on this chip
+// for a given operand content, with no memory traffic in the loop.
+__global__ __launch_bounds__(256) void mfma_probe_kernel(const u32x4* in, float* out, uint32_t iters) {
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    union { u32x4 u; bf16x8 v; } fa[4], fb[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        fa[i].u = in[(threadIdx.x * 8 + i) & 4095];
+        fb[i].u = in[(threadIdx.x * 8 + 4 + i + blockIdx.x) & 4095];
+    }
+    for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i].v, fb[j].v, acc[i * 4 + j], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += acc[i][r];
+    out[blockIdx.x * 256 + threadIdx.x] = sum;
+}
+
 }  // namespace
+
+hipError_t launch_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, uint32_t iters,
+                             hipStream_t stream) {
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3(n_workgroups), dim3(256), 0, stream,
+                       static_cast<const u32x4*>(operands), out, iters);
+    return hipGetLastError();
+}
 
 hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook hook, void* user) {
     (void)n_cus;

@@ -953,6 +953,14 @@ int fluxmoe_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_w
     return FLUXMOE_OK;
 }
 
+int fluxmoe_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, uint32_t iters, void* stream) {
+    if (!operands || !out) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    if ((uintptr_t(operands) & 15) || (uintptr_t(out) & 3)) return set_error(FLUXMOE_EINVAL, "operands must be 16-byte aligned");
+    if (n_workgroups == 0 || n_workgroups > (1u << 16) || iters == 0) return set_error(FLUXMOE_EINVAL, "bad n_workgroups or iters");
+    HIPCHECK(launch_mfma_probe(operands, out, n_workgroups, iters, static_cast<hipStream_t>(stream)));
+    return FLUXMOE_OK;
+}
+
 int fluxmoe_profile_enable(fluxmoe_ctx* c, int on) {
     if (!c) return set_error(FLUXMOE_EINVAL, "ctx is NULL");
     c->profiling = on != 0;

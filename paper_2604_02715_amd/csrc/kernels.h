@@ -98,5 +98,7 @@ struct FfnArgs {
 // (kinds: 1 grouping, 2 gate/up product + SwiGLU, 3 down product, 4 combine)
 typedef void (*SpanHook)(void* user, int kind, int begin, hipStream_t stream);
 hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHook hook, void* user);
+hipError_t launch_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, uint32_t iters,
+                             hipStream_t stream);
 
 }  // namespace fluxmoe
