@@ -133,10 +133,94 @@ template <int MI> struct RingDepth { static constexpr int value = MI >= 4 ? 3 : 
 // the smaller body a kernel for tiles of 16 MI rows also carries (for tiles with few rows)
 template <int MI> struct SmallerBody { static constexpr int value = MI == 6 ? 4 : (MI >= 2 ? MI / 2 : 1); };
 
+// Shared A blocks: the four wavefronts of a workgroup multiply the same rows of A, so a block of
+// kABlock k values of the tile's rows is loaded once per workgroup into LDS (two buffers) instead of
+// once per wavefront from L2 (where it costs 0.75 bytes of requests per weight byte streamed).
+constexpr int kABlock = 128;                 // k per block = 4 chunks
+constexpr int kAPitch = kABlock + 8;         // LDS row pitch in elements (272 bytes: conflict-free 16-byte reads)
+
 // One wavefront's product C[16*MI rows][128 columns] = A[rows][k range] * B[k range][strip].
 template <int MI>
 struct StripGemm {
     f32x4 acc[MI][8];
+
+    static constexpr int kABufElems = 16 * MI * kAPitch;     // one LDS buffer
+
+    __device__ __forceinline__ static void load_b(uint4 (&b)[8], const uint16_t* bcol, size_t ldb, uint32_t k0) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) b[r] = *reinterpret_cast<const uint4*>(bcol + size_t(k0 + r) * ldb);
+    }
+
+    __device__ __forceinline__ void mma_b(const uint4 (&b)[8], const uint4 (&a)[MI]) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            Frag f;
+            const uint32_t sel = (c & 1) ? 0x07060302u : 0x05040100u;
+            f.u.x = __builtin_amdgcn_perm(comp(b[1], c >> 1), comp(b[0], c >> 1), sel);
+            f.u.y = __builtin_amdgcn_perm(comp(b[3], c >> 1), comp(b[2], c >> 1), sel);
+            f.u.z = __builtin_amdgcn_perm(comp(b[5], c >> 1), comp(b[4], c >> 1), sel);
+            f.u.w = __builtin_amdgcn_perm(comp(b[7], c >> 1), comp(b[6], c >> 1), sel);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                Frag fa;
+                fa.u = a[mi];
+                acc[mi][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v, f.v, acc[mi][c], 0, 0, 0);
+            }
+        }
+    }
+
+    // The first n_blocks * kABlock k values of the range with A shared through LDS.  Every wavefront
+    // of the workgroup must call this with the same arow_ld, k_begin and n_blocks (it contains
+    // barriers).  arow_ld[i] points at row 16 i + tid / 16 of the tile (clamped to the last row),
+    // already advanced by 8 (tid % 16) elements: the thread's 16-byte piece of each block row.
+    // B runs through a four-deep register ring as in run().
+    __device__ __forceinline__ void run_shared(const uint16_t* const (&arow_ld)[MI], uint16_t* abuf,
+                                               const uint16_t* bcol, size_t ldb, uint32_t k_begin,
+                                               uint32_t n_blocks, int lane, int tid) {
+        if (n_blocks == 0) return;
+        const uint32_t kg = 8u * (uint32_t(lane) >> 4);
+        const uint32_t kb = k_begin + kg;
+        const int a_st = (tid >> 4) * kAPitch + 8 * (tid & 15);                 // + 16 i rows
+        const int a_fr = (lane & 15) * kAPitch + int(kg);                       // + 16 mi rows, + 32 c
+        uint4 areg[MI];
+        uint4 bst[4][8];
+        auto a_load = [&](uint32_t blk) __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i) areg[i] = *reinterpret_cast<const uint4*>(arow_ld[i] + k_begin + blk * kABlock);
+        };
+        auto a_store = [&](uint16_t* buf) __attribute__((always_inline)) {
+#pragma unroll
+            for (int i = 0; i < MI; ++i) *reinterpret_cast<uint4*>(buf + a_st + 16 * i * kAPitch) = areg[i];
+        };
+        // one block of four chunks; PREFETCH: all four B loads three chunks ahead are inside the
+        // shared range and the next A block exists
+        auto block = [&](const uint16_t* cur, uint16_t* nxt, uint32_t blk, auto PREFETCH) __attribute__((always_inline)) {
+            if (PREFETCH.value) a_load(blk + 1);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t chunk = blk * 4 + c;
+                if (PREFETCH.value || chunk + 3 < n_blocks * 4) load_b(bst[(c + 3) & 3], bcol, ldb, kb + (chunk + 3) * kChunk);
+                uint4 af[MI];
+#pragma unroll
+                for (int mi = 0; mi < MI; ++mi)
+                    af[mi] = *reinterpret_cast<const uint4*>(cur + a_fr + 16 * mi * kAPitch + 32 * c);
+                mma_b(bst[c], af);
+            }
+            if (PREFETCH.value) a_store(nxt);
+            __syncthreads();
+        };
+        a_load(0);
+#pragma unroll
+        for (int c = 0; c < 3; ++c) load_b(bst[c], bcol, ldb, kb + c * kChunk);
+        a_store(abuf);
+        __syncthreads();
+        uint32_t blk = 0;
+        for (; blk + 1 < n_blocks; ++blk)
+            block(abuf + (blk & 1) * kABufElems, abuf + ((blk + 1) & 1) * kABufElems, blk,
+                  std::integral_constant<bool, true>{});
+        block(abuf + (blk & 1) * kABufElems, abuf + ((blk + 1) & 1) * kABufElems, blk,
+              std::integral_constant<bool, false>{});
+    }
 
     struct Stage {
         uint4 b[8];      // the lane's 8 rows x 8 columns of B
@@ -184,7 +268,7 @@ struct StripGemm {
     __device__ __forceinline__ void run(const uint16_t* const (&arow)[MI], const uint16_t* bcol,
                                         size_t ldb, uint32_t k_begin, uint32_t k_end, int lane) {
         constexpr int kStages = RingDepth<MI>::value;
-        zero();
+        if (k_begin >= k_end) return;
         const uint32_t kg = 8u * (uint32_t(lane) >> 4);
         const uint32_t n = (k_end - k_begin) / kChunk;
         const uint32_t kb = k_begin + kg;
@@ -255,7 +339,7 @@ __device__ __forceinline__ bool tile_info(const FfnArgs& a, uint32_t tile, TileI
 // SwiGLU and stores.  Splitting the two matrices over two wavefronts halves the accumulator
 // registers per wavefront, which is what leaves room for the deep load ring.
 template <int MI>
-__device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileInfo& t, float (*xch)[64]) {
+__device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileInfo& t, float (*xch)[64], uint16_t* abuf) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int pair = wave >> 1;
@@ -275,8 +359,19 @@ __device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileIn
     const size_t mat = size_t(a.H) * a.F;
     const uint16_t* w = a.slots13 + size_t(t.slot) * 2 * mat + size_t(mat_id) * mat;
 
+    // the loader's rows of the shared A blocks: row 16 i + tid / 16, piece tid % 16
+    const uint16_t* arow_ld[MI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int32_t r = min(i * 16 + int(threadIdx.x >> 4), t.rows - 1);
+        const int32_t pr = a.sorted_pair[t.row0 + r];
+        arow_ld[i] = a.tokens + size_t(uint32_t(pr) / a.K) * a.H + 8 * (threadIdx.x & 15);
+    }
     StripGemm<MI> g;
-    g.run(arow, w + (col_ok ? n0 : a.F - 8), a.F, 0, a.H, lane);
+    g.zero();
+    const uint32_t n_blocks = a.H / kABlock;
+    g.run_shared(arow_ld, abuf, w + (col_ok ? n0 : a.F - 8), a.F, 0, n_blocks, lane, threadIdx.x);
+    g.run(arow, w + (col_ok ? n0 : a.F - 8), a.F, n_blocks * kABlock, a.H, lane);
 
     if (mat_id == 1) {
 #pragma unroll
@@ -317,22 +412,22 @@ __device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileIn
 template <int MI>
 __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
     __shared__ float xch[2 * MI * 8 * 4][64];     // [pair][mi, c, r][lane]
+    __shared__ __align__(16) uint16_t abuf[2 * StripGemm<MI>::kABufElems];
     TileInfo t;
     if (!tile_info(a, blockIdx.y, t)) return;     // uniform over the workgroup
     constexpr int kSmall = SmallerBody<MI>::value;
-    if (kSmall < MI && t.rows <= 16 * kSmall) gemm1_swiglu_body<kSmall>(a, t, xch);
-    else gemm1_swiglu_body<MI>(a, t, xch);
+    if (kSmall < MI && t.rows <= 16 * kSmall) gemm1_swiglu_body<kSmall>(a, t, xch, abuf);
+    else gemm1_swiglu_body<MI>(a, t, xch, abuf);
 }
 
 // y[split][row][n] = h[row][k range] W2[k range][n]
 template <int MI>
-__device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t) {
+__device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t, uint16_t* abuf) {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const uint32_t strip = blockIdx.x * 4 + wave;
     const uint32_t n0 = strip * kStrip + 8u * (lane & 15);
-    if (strip * kStrip >= a.H) return;
-    const bool col_ok = n0 < a.H;
+    const bool col_ok = n0 < a.H;                 // wavefronts past the last strip still run (barriers below)
     const uint32_t split = blockIdx.z;
     const uint32_t k_per = ((a.F + a.ksplit - 1) / a.ksplit + kChunk - 1) / kChunk * kChunk;
     const uint32_t k_begin = min(a.F, split * k_per);
@@ -346,8 +441,17 @@ __device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t) 
     }
     const uint16_t* w2 = a.slots2 + size_t(t.slot) * a.F * a.H;
 
+    const uint16_t* arow_ld[MI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+        const int32_t r = min(i * 16 + int(threadIdx.x >> 4), t.rows - 1);
+        arow_ld[i] = a.hbuf + size_t(t.row0 + r) * a.F + 8 * (threadIdx.x & 15);
+    }
     StripGemm<MI> g;
-    g.run(arow, w2 + (col_ok ? n0 : a.H - 8), a.H, k_begin, k_end, lane);
+    g.zero();
+    const uint32_t n_blocks = (k_end - k_begin) / kABlock;
+    g.run_shared(arow_ld, abuf, w2 + (col_ok ? n0 : a.H - 8), a.H, k_begin, n_blocks, lane, threadIdx.x);
+    g.run(arow, w2 + (col_ok ? n0 : a.H - 8), a.H, k_begin + n_blocks * kABlock, k_end, lane);
 
     if (!col_ok) return;
     float* y = a.ybuf + size_t(split) * a.pairs_cap * a.H;
@@ -367,11 +471,12 @@ __device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t) 
 
 template <int MI>
 __global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
+    __shared__ __align__(16) uint16_t abuf[2 * StripGemm<MI>::kABufElems];
     TileInfo t;
     if (!tile_info(a, blockIdx.y, t)) return;
     constexpr int kSmall = SmallerBody<MI>::value;
-    if (kSmall < MI && t.rows <= 16 * kSmall) gemm2_body<kSmall>(a, t);
-    else gemm2_body<MI>(a, t);
+    if (kSmall < MI && t.rows <= 16 * kSmall) gemm2_body<kSmall>(a, t, abuf);
+    else gemm2_body<MI>(a, t, abuf);
 }
 
 // ------------------------------------------------------------------ large row tiles (MFMA bound)
