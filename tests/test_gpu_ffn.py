@@ -152,3 +152,13 @@ def test_shared_expert_added_on_top_of_the_routed_experts():
         assert offn.rel_frobenius(out.cpu().numpy(), routed + shared) <= TOL
     finally:
         pool.close()
+
+
+def test_mfma_probe_counts_what_it_claims():
+    """The MFMA-only measurement aid: with all-ones operands every accumulator element grows by 16
+    per MFMA (K = 16), so a lane's checksum is 16 accumulators x 16 elements x 16 x iters."""
+    ones = torch.ones(32768, dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros(3 * 256, dtype=torch.float32, device="cuda")
+    B.fluxmoe_mfma_probe(ones.data_ptr(), out.data_ptr(), 3, 5)
+    torch.cuda.synchronize()
+    assert torch.all(out == 16 * 16 * 16 * 5)
