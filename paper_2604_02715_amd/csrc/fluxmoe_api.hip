@@ -96,8 +96,8 @@ struct fluxmoe_ctx {
     hipEvent_t ev_half_done[2] = {};        // last decode that read the half
     bool half_done_valid[2] = {false, false};
     // launch shape of the decode kernel (FLUXMOE_DECODE_WAVES / FLUXMOE_DECODE_WG_PER_CU override)
-    int tune_waves = 16;
-    int tune_wg_per_cu = 8;
+    int tune_waves = 8;
+    int tune_wg_per_cu = 16;
     int tune_chunk = 1;
     int tune_tiled_waves = 8;             // FLUXMOE_FFN_TILED_WAVES: 8 (64 x 128 per wavefront) or 4 (128 x 128)
     // optional kernel timing (fluxmoe_profile_*)
