@@ -162,3 +162,29 @@ def test_mfma_probe_counts_what_it_claims():
     B.fluxmoe_mfma_probe(ones.data_ptr(), out.data_ptr(), 3, 5)
     torch.cuda.synchronize()
     assert torch.all(out == 16 * 16 * 16 * 5)
+
+
+def test_empty_batch_and_fully_skipped_batch():
+    """T = 0 enqueues nothing; with no expert mapped and the skip flag every pair is ignored: the
+    result is zero, or the previous contents with the accumulate flag, and no error is flagged."""
+    from gpu_common import build_pool
+    cfg = inputs.CONFIGS["c1_tiny"]
+    pool, dense = build_pool(cfg)
+    try:
+        x = inputs.activations(cfg).cuda()
+        ids, g = inputs.routing(cfg)
+        idd, gd = torch.from_numpy(ids).cuda(), torch.from_numpy(g).cuda()
+        out = torch.full((cfg.tokens, cfg.hidden), 3.0, dtype=torch.float32, device="cuda")
+        pool.reset_page_table()
+        B.fluxmoe_expert_ffn(pool.ctx, 0, x.data_ptr(), 0, idd.data_ptr(), gd.data_ptr(), cfg.top_k,
+                             pool.page_table.data_ptr(), out.data_ptr(), 0, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.all(out == 3.0)
+        pool.expert_ffn(0, x, idd, gd, out, B.FFN_SKIP_UNMAPPED | B.FFN_ACCUMULATE)
+        torch.cuda.synchronize()
+        assert torch.all(out == 3.0) and pool.device_errors() == 0
+        pool.expert_ffn(0, x, idd, gd, out, B.FFN_SKIP_UNMAPPED)
+        torch.cuda.synchronize()
+        assert torch.all(out == 0.0) and pool.device_errors() == 0
+    finally:
+        pool.close()
