@@ -919,6 +919,249 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         }
 }
 
+// Third variant of the tiled kernel: both operands go from global memory straight into LDS
+// (global_load_lds, 16 bytes per lane, no register staging, no LDS write instructions) and B stays
+// row-major [k][n] there; its MFMA fragments are formed by the transposing LDS read
+// (ds_read_b64_tr_b16: within 16 lanes, lane L receives element L % 4 of the four 8-byte groups that
+// lanes L / 4, 4 + L / 4, 8 + L / 4, 12 + L / 4 point at).  Because an LDS-direct load fills 1 KiB
+// contiguously (lane l at +16 l), rows cannot be padded; bank conflicts are avoided by choosing
+// which global piece each lane fetches: A rows (128 bytes = 8 pieces) hold piece p ^ ((row >> 1) & 7)
+// at position p; B rows (512 bytes = 8 units of 32 columns) hold unit u ^ (k & 3) at position u.
+// LDS: [A stage 0 | A stage 1 | B stage 0 | B stage 1], 32 KiB each.  Same eight wavefronts, wave
+// tiles and schedule as gemm_tiled_kernel; the loads of step s + 1 are issued right after the
+// barrier of step s - 1 and must have landed (vmcnt) before the barrier of step s.
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+
+template <int MODE>
+__global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
+    extern __shared__ __align__(16) uint16_t lds[];
+    const uint32_t K = MODE == 1 ? a.H : a.F;
+    const uint32_t N = MODE == 1 ? a.F : a.H;
+    const uint32_t ncols_tile = MODE == 1 ? 128u : 256u;
+    const uint32_t n_ct = (N + ncols_tile - 1) / ncols_tile;
+    const uint32_t n_rt = uint32_t(a.n_tiles[0]);
+    const uint32_t n_sn = (n_ct + kSuperN - 1) / kSuperN;
+    const uint32_t xcd = blockIdx.x % 8u, jj = blockIdx.x / 8u;
+    const uint32_t st = (jj / (kSuperM * kSuperN)) * 8u + xcd;
+    const uint32_t within = jj % (kSuperM * kSuperN);
+    const uint32_t row_tile = (st / n_sn) * kSuperM + within / kSuperN;
+    const uint32_t col_tile = (st % n_sn) * kSuperN + within % kSuperN;
+    if (row_tile >= n_rt || col_tile >= n_ct) return;
+    TileInfo t;
+    if (!tile_info(a, row_tile, t)) return;
+    const uint32_t n_base = col_tile * ncols_tile;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int q = lane & 31, h = lane >> 5;
+    constexpr int kStageBytes = 32768;
+    uint8_t* const lds_b8 = reinterpret_cast<uint8_t*>(lds);
+
+    // ---- global sources of this lane's LDS-direct loads (4 for A, 4 for B per step): 32-bit byte
+    // offsets from bases that are uniform over the workgroup
+    const uint8_t* const a_base = reinterpret_cast<const uint8_t*>(MODE == 1 ? a.tokens : a.hbuf);
+    uint32_t a_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r_lds = 8 * (wave * 4 + i) + (lane >> 3);                 // row of the A tile
+        const int piece = (lane & 7) ^ ((r_lds >> 1) & 7);                  // global 16-byte piece held at position lane & 7
+        const int32_t r = min(r_lds, t.rows - 1);
+        uint32_t row_elems;
+        if (MODE == 1) row_elems = (uint32_t(a.sorted_pair[t.row0 + r]) / a.K) * a.H;
+        else row_elems = uint32_t(t.row0 + r) * a.F;
+        a_off[i] = 2u * (row_elems + 8u * piece);
+    }
+    const size_t mat = size_t(a.H) * a.F;
+    const uint8_t* const b_base = reinterpret_cast<const uint8_t*>(
+        MODE == 1 ? a.slots13 + size_t(t.slot) * 2 * mat : a.slots2 + size_t(t.slot) * mat);
+    uint32_t b_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k_lds = 2 * (wave * 4 + i) + (lane >> 5);                 // k row of the B tile
+        const int pp = lane & 31;                                           // physical 16-byte piece in the row
+        const int unit = (pp >> 2) ^ (k_lds & 3);                           // logical unit of 32 columns
+        const uint32_t c = 32u * unit + 8u * (pp & 3);                      // column inside the 256-column tile
+        uint32_t elems;
+        if (MODE == 1) elems = (c >= 128 ? uint32_t(mat) : 0u) + min(n_base + (c & 127u), N - 8);
+        else elems = min(n_base + c, N - 8);
+        b_off[i] = 2u * (elems + uint32_t(k_lds) * N);
+    }
+    // stage_off: 0 or kStageBytes, uniform.  The load is written as inline assembly on purpose: with
+    // the compiler's builtin, every later LDS read waits for all outstanding LDS-direct loads
+    // (it cannot see that they go to the other stage), which serialises the whole step.  Here the
+    // only wait is the explicit vmcnt(0) before the step's barrier.
+    const uint32_t lds_base = uint32_t(uintptr_t((__attribute__((address_space(3))) void*)lds));
+    auto dma16 = [&](const uint8_t* gptr, uint32_t lds_addr) __attribute__((always_inline)) {
+        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                     :: "v"(gptr), "s"(lds_addr) : "memory", "m0");
+    };
+    auto dma_item = [&](uint32_t k0, int stage_off, int n) __attribute__((always_inline)) {
+        if (n < 4) dma16(a_base + size_t(k0) * 2 + a_off[n], lds_base + stage_off + (wave * 4 + n) * 1024);
+        else dma16(b_base + size_t(k0) * N * 2 + b_off[n - 4],
+                   lds_base + 2 * kStageBytes + stage_off + (wave * 4 + n - 4) * 1024);
+    };
+
+    // ---- fragment addresses (bytes from the start of stage 0 of the operand's region)
+    int a_addr[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int R = wm * 64 + 32 * i + q;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) a_addr[i][ks] = R * 128 + 16 * ((2 * ks + h) ^ ((R >> 1) & 7));
+    }
+    // B fragment j of sub-step ks, read t: row 16 ks + 8 h + 4 t + e, unit u(j) ^ e, bytes 32 nh + 8 g
+    const int e = (lane & 15) >> 2, g = lane & 3, nh = (lane >> 4) & 1;
+    int b_addr[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int unit = MODE == 1 ? ((((2 * wn + (j & 1)) ^ e)) + 4 * (j >> 1)) : (4 * wn + (j ^ e));
+        b_addr[j] = 2 * kStageBytes + (8 * h + e) * 512 + 64 * unit + 32 * nh + 8 * g;
+    }
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    bf16x8 fa[2][2];
+    i16x4 fb_lo[2][4], fb_hi[2][4];
+    // item n of the 10 fragment reads of sub-step ks from `stage` into register set `set`:
+    // 0..1 A tiles, 2..9 the two halves (k 0..3 and 4..7 of the lane's 8) of the four B fragments
+    // OTHER: read from the stage the address registers do not point at (they are toggled per step)
+    auto lfrag_item = [&](int other, int ks, int set, int n) __attribute__((always_inline)) {
+        if (n < 2) {
+            fa[set][n] = *reinterpret_cast<const bf16x8*>(lds_b8 + (a_addr[n][ks] ^ (other ? kStageBytes : 0)));
+        } else {
+            const int j = (n - 2) >> 1, tt = (n - 2) & 1;
+            const i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (lds_i16x4*)(lds_b8 + ((b_addr[j] ^ (other ? kStageBytes : 0)) + ks * 8192 + tt * 2048)));
+            if (tt == 0) fb_lo[set][j] = v; else fb_hi[set][j] = v;
+        }
+    };
+    typedef short i16x8 __attribute__((ext_vector_type(8)));
+    auto mfma_item = [&](int set, int n) __attribute__((always_inline)) {
+        const int i = n >> 2, j = n & 3;
+        const i16x8 full = __builtin_shufflevector(fb_lo[set][j], fb_hi[set][j], 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], __builtin_bit_cast(bf16x8, full), acc[i][j], 0, 0, 0);
+    };
+
+    const uint32_t n_steps = K / kTK;
+    // One step on the stage the address registers point at.  DMA: fetch step s + 1 into the other
+    // stage (issued after the barrier of the previous step, i.e. during this step's sub-steps 0 and
+    // 1); NEXT: another step follows (its first fragments are read after the barrier).
+    // DMA_B: the B half of step s + 1 goes to the other stage during sub-step 0; DMA_A: the A half of
+    // step s + 2 goes to this step's own stage right after the barrier (sub-step 3), when nobody
+    // reads it any more; NEXT: another step follows.
+    auto step = [&](int other_off, uint32_t k_next, auto DMA_B, auto DMA_A, auto NEXT) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {                         // sub-step 0 (set 0)
+            mfma_item(0, n);
+            lfrag_item(0, 1, 1, n);
+            if (DMA_B.value && (n & 1)) dma_item(k_next, other_off, 4 + (n >> 1));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lfrag_item(0, 1, 1, 8);
+        lfrag_item(0, 1, 1, 9);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {                         // sub-step 1 (set 1)
+            mfma_item(1, n);
+            lfrag_item(0, 2, 0, n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lfrag_item(0, 2, 0, 8);
+        lfrag_item(0, 2, 0, 9);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {                         // sub-step 2 (set 0)
+            mfma_item(0, n);
+            lfrag_item(0, 3, 1, n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        lfrag_item(0, 3, 1, 8);
+        lfrag_item(0, 3, 1, 9);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wavefront's part of the next stage has landed
+        __syncthreads();                                      // all reads of this stage are in registers
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {                         // sub-step 3 (set 1)
+            mfma_item(1, n);
+            if (NEXT.value) lfrag_item(1, 0, 0, n);
+            if (DMA_A.value && (n & 1)) dma_item(k_next + kTK, other_off ^ kStageBytes, n >> 1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (NEXT.value) {
+            lfrag_item(1, 0, 0, 8);
+            lfrag_item(1, 0, 0, 9);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // point the address registers at the other stage
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) a_addr[i][ks] ^= kStageBytes;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b_addr[j] ^= kStageBytes;
+    };
+    using Yes = std::integral_constant<bool, true>;
+    using No = std::integral_constant<bool, false>;
+
+#pragma unroll
+    for (int n = 0; n < 8; ++n) dma_item(0, 0, n);
+    if (n_steps > 1) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n) dma_item(kTK, kStageBytes, n);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+#pragma unroll
+    for (int n = 0; n < 10; ++n) lfrag_item(0, 0, 0, n);
+    int other_off = kStageBytes;
+    uint32_t s = 0;
+    for (; s + 2 < n_steps; ++s) {
+        step(other_off, (s + 1) * kTK, Yes{}, Yes{}, Yes{});
+        other_off ^= kStageBytes;
+    }
+    if (s + 1 < n_steps) {
+        step(other_off, (s + 1) * kTK, Yes{}, No{}, Yes{});
+        other_off ^= kStageBytes;
+    }
+    step(other_off, 0, No{}, No{}, No{});
+
+    // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4;
+    // fragment j of this wavefront holds tile columns 128 wn + 32 j + q (MODE 2) or, in MODE 1,
+    // gate (j = 0, 1) and up (j = 2, 3) of h columns 64 wn + 32 (j & 1) + q
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int32_t row = wm * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+            if (row >= t.rows) continue;
+            if (MODE == 1) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const uint32_t col = n_base + 64u * wn + 32u * j + q;
+                    if (col >= N) continue;
+                    const float ga_ = acc[i][j][r];
+                    const float up = acc[i][j + 2][r];
+                    const float hv = ga_ / (1.0f + __expf(-ga_)) * up;
+                    a.hbuf[size_t(t.row0 + row) * a.F + col] = uint16_t(f32_to_bf16_rne(hv));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t col = n_base + 128u * wn + 32u * j + q;
+                    if (col >= N) continue;
+                    a.ybuf[size_t(t.row0 + row) * a.H + col] = acc[i][j][r];
+                }
+            }
+        }
+}
+
 // out[t][:] (+)= sum_k gate * sum_split y
 __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
     const uint32_t tok = blockIdx.y;
@@ -996,6 +1239,7 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
     if (a.m_tile == 256) {
         const size_t lds_bytes = 4 * size_t(kTM) * kLdsPitch * sizeof(uint16_t);
         const bool four = a.tiled_waves == 4;
+        const bool d2l = a.tiled_waves == 2;
         static bool attr_set = false;
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<1>),
@@ -1010,6 +1254,12 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled4_kernel<2>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
             if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<2>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
+            if (e != hipSuccess) return e;
             attr_set = true;
         }
         mark(2, 1);
@@ -1018,11 +1268,13 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
             const uint32_t supers = (n_sm * n_sn + 7) / 8 * 8;      // whole rounds over the 8 XCDs
             return dim3(supers * kSuperM * kSuperN, 1, 1);
         };
-        if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<1>, grid_for((a.F + 127) / 128), dim3(256), lds_bytes, stream, a);
+        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), 131072, stream, a);
+        else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<1>, grid_for((a.F + 127) / 128), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), lds_bytes, stream, a);
         mark(2, 0);
         mark(3, 1);
-        if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<2>, grid_for((a.H + 255) / 256), dim3(256), lds_bytes, stream, a);
+        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), 131072, stream, a);
+        else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<2>, grid_for((a.H + 255) / 256), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), lds_bytes, stream, a);
         mark(3, 0);
         const dim3 gc2((a.H / 4 + 255) / 256, a.T, 1);

@@ -99,7 +99,8 @@ struct fluxmoe_ctx {
     int tune_waves = 8;
     int tune_wg_per_cu = 16;
     int tune_chunk = 1;
-    int tune_tiled_waves = 8;             // FLUXMOE_FFN_TILED_WAVES: 8 (64 x 128 per wavefront) or 4 (128 x 128)
+    int tune_tiled_waves = 2;             // FLUXMOE_FFN_TILED_WAVES: 2 = LDS-direct loads (default), 8 = register-staged,
+                                          // 4 = register-staged with four wavefronts of 128 x 128
     // optional kernel timing (fluxmoe_profile_*)
     bool profiling = false;
     struct Span { hipEvent_t a, b; int kind; };
@@ -281,7 +282,7 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     }
     if (const char* v = std::getenv("FLUXMOE_FFN_TILED_WAVES")) {
         const int w = std::atoi(v);
-        if (w == 4 || w == 8) c->tune_tiled_waves = w;
+        if (w == 2 || w == 4 || w == 8) c->tune_tiled_waves = w;
     }
     *out_ctx = c;
     g_err[0] = 0;

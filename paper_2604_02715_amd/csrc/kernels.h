@@ -91,7 +91,8 @@ struct FfnArgs {
     float* ybuf;                 // FP32 [ksplit][pairs_cap][H]
     uint32_t* error_word;
     uint32_t pairs_cap, tiles_cap, m_tile, ksplit;
-    uint32_t tiled_waves;        // wavefronts of the LDS-tiled kernels (m_tile 256): 8 or 4
+    uint32_t tiled_waves;        // variant of the LDS-tiled kernels (m_tile 256): 2 LDS-direct loads, 8 or 4
+                                 // wavefronts with register-staged loads
 };
 
 // hook(user, kind, begin, stream) is called around every kernel when timing is on

@@ -79,14 +79,20 @@ def test_shapes(kw):
     run_ffn_case(inputs.scaled(inputs.CONFIGS["c1_tiny"], **kw), seed=1)
 
 
-def test_four_wavefront_variant_of_the_tiled_kernels(monkeypatch):
-    """FLUXMOE_FFN_TILED_WAVES=4 selects the 128 x 128 per-wavefront variant; same results."""
-    kw = dict(tokens=700, top_k=2, n_experts=3, n_slots=3, hidden=192, ffn=320)
+@pytest.mark.parametrize("kw", [
+    dict(tokens=700, top_k=2, n_experts=3, n_slots=3, hidden=192, ffn=320),
+    dict(tokens=600, top_k=1, n_experts=2, n_slots=2, hidden=256, ffn=576),
+])
+def test_variants_of_the_tiled_kernels(monkeypatch, kw):
+    """FLUXMOE_FFN_TILED_WAVES selects the variant of the LDS-tiled kernels: 2 (default) loads both
+    operands straight into LDS, 8 and 4 stage them through registers with eight or four wavefronts.
+    All accumulate over k in the same order, so they must agree to rounding."""
     cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], **kw)
-    eight = run_ffn_case(cfg, seed=1)
-    monkeypatch.setenv("FLUXMOE_FFN_TILED_WAVES", "4")
-    four = run_ffn_case(cfg, seed=1)
-    assert offn.rel_frobenius(four, eight) < 1e-5
+    default = run_ffn_case(cfg, seed=1)
+    for variant in ("8", "4", "2"):
+        monkeypatch.setenv("FLUXMOE_FFN_TILED_WAVES", variant)
+        other = run_ffn_case(cfg, seed=1)
+        assert offn.rel_frobenius(other, default) < 1e-5, variant
 
 
 def test_wave_mode_accumulates_to_the_single_shot_result():
