@@ -927,9 +927,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 // contiguously (lane l at +16 l), rows cannot be padded; bank conflicts are avoided by choosing
 // which global piece each lane fetches: A rows (128 bytes = 8 pieces) hold piece p ^ ((row >> 1) & 7)
 // at position p; B rows (512 bytes = 8 units of 32 columns) hold unit u ^ (k & 3) at position u.
-// LDS: [A stage 0 | A stage 1 | B stage 0 | B stage 1], 32 KiB each.  Same eight wavefronts, wave
-// tiles and schedule as gemm_tiled_kernel; the loads of step s + 1 are issued right after the
-// barrier of step s - 1 and must have landed (vmcnt) before the barrier of step s.
+// LDS: [A stage 0 | A stage 1 | B stage 0 | B stage 1 | B stage 2], 32 KiB each = all 160 KiB.  Same
+// eight wavefronts, wave tiles and sub-step schedule as gemm_tiled_kernel.
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
 
@@ -997,10 +996,12 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
         asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                      :: "v"(gptr), "s"(lds_addr) : "memory", "m0");
     };
-    auto dma_item = [&](uint32_t k0, int stage_off, int n) __attribute__((always_inline)) {
-        if (n < 4) dma16(a_base + size_t(k0) * 2 + a_off[n], lds_base + stage_off + (wave * 4 + n) * 1024);
-        else dma16(b_base + size_t(k0) * N * 2 + b_off[n - 4],
-                   lds_base + 2 * kStageBytes + stage_off + (wave * 4 + n - 4) * 1024);
+    // a_stage_off / b_stage_off: byte offset of the destination stage inside the operand's region, uniform
+    auto dma_a = [&](uint32_t k0, int a_stage_off, int n) __attribute__((always_inline)) {
+        dma16(a_base + size_t(k0) * 2 + a_off[n], lds_base + a_stage_off + (wave * 4 + n) * 1024);
+    };
+    auto dma_b = [&](uint32_t k0, int b_stage_off, int n) __attribute__((always_inline)) {
+        dma16(b_base + size_t(k0) * N * 2 + b_off[n], lds_base + 2 * kStageBytes + b_stage_off + (wave * 4 + n) * 1024);
     };
 
     // ---- fragment addresses (bytes from the start of stage 0 of the operand's region)
@@ -1032,14 +1033,16 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     i16x4 fb_lo[2][4], fb_hi[2][4];
     // item n of the 10 fragment reads of sub-step ks from `stage` into register set `set`:
     // 0..1 A tiles, 2..9 the two halves (k 0..3 and 4..7 of the lane's 8) of the four B fragments
-    // OTHER: read from the stage the address registers do not point at (they are toggled per step)
+    // OTHER: read from the next step's stage instead of the one the address registers point at
+    // (A: the other of two stages; B: b_next_delta bytes further in its ring of three)
+    int b_next_delta = kStageBytes;
     auto lfrag_item = [&](int other, int ks, int set, int n) __attribute__((always_inline)) {
         if (n < 2) {
             fa[set][n] = *reinterpret_cast<const bf16x8*>(lds_b8 + (a_addr[n][ks] ^ (other ? kStageBytes : 0)));
         } else {
             const int j = (n - 2) >> 1, tt = (n - 2) & 1;
             const i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (lds_i16x4*)(lds_b8 + ((b_addr[j] ^ (other ? kStageBytes : 0)) + ks * 8192 + tt * 2048)));
+                (lds_i16x4*)(lds_b8 + ((b_addr[j] + (other ? b_next_delta : 0)) + ks * 8192 + tt * 2048)));
             if (tt == 0) fb_lo[set][j] = v; else fb_hi[set][j] = v;
         }
     };
@@ -1051,18 +1054,22 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     };
 
     const uint32_t n_steps = K / kTK;
-    // One step on the stage the address registers point at.  DMA: fetch step s + 1 into the other
-    // stage (issued after the barrier of the previous step, i.e. during this step's sub-steps 0 and
-    // 1); NEXT: another step follows (its first fragments are read after the barrier).
-    // DMA_B: the B half of step s + 1 goes to the other stage during sub-step 0; DMA_A: the A half of
-    // step s + 2 goes to this step's own stage right after the barrier (sub-step 3), when nobody
-    // reads it any more; NEXT: another step follows.
-    auto step = [&](int other_off, uint32_t k_next, auto DMA_B, auto DMA_A, auto NEXT) __attribute__((always_inline)) {
+    // Step s multiplies A stage s % 2 and B stage s % 3.  After its barrier nobody reads those
+    // stages any more, so sub-step 3 issues the A loads of step s + 2 into the same A stage and
+    // sub-step 0 of the next step issues the B loads of step s + 3 into the same B stage: B, whose
+    // first reader in an XCD goes to HBM, is fetched two steps ahead, A (mostly L2 hits) one.
+    // Loads return in order, so waiting until at most 4 are outstanding before the barrier of
+    // step s leaves only the B loads of step s + 2 in flight.
+    // LOAD_B: B of step s + 2 (issued in sub-step 0); LOAD_A: A of step s + 2 (after the barrier);
+    // NEXT: another step follows.
+    int a_own = 0, b_own = 0;                                // byte offsets of this step's stages
+    auto step = [&](uint32_t k0, auto LOAD_B, auto LOAD_A, auto NEXT) __attribute__((always_inline)) {
+        const int b_plus2 = b_own >= kStageBytes ? b_own - kStageBytes : b_own + 2 * kStageBytes;   // stage of step s + 2
 #pragma unroll
         for (int n = 0; n < 8; ++n) {                         // sub-step 0 (set 0)
             mfma_item(0, n);
             lfrag_item(0, 1, 1, n);
-            if (DMA_B.value && (n & 1)) dma_item(k_next, other_off, 4 + (n >> 1));
+            if (LOAD_B.value && (n & 1)) dma_b(k0 + 2 * kTK, b_plus2, n >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
         lfrag_item(0, 1, 1, 8);
@@ -1085,13 +1092,14 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
         }
         lfrag_item(0, 3, 1, 8);
         lfrag_item(0, 3, 1, 9);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wavefront's part of the next stage has landed
-        __syncthreads();                                      // all reads of this stage are in registers
+        if (LOAD_B.value) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");   // all but this step's own B loads have landed
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                                      // all reads of this step's stages are in registers
 #pragma unroll
         for (int n = 0; n < 8; ++n) {                         // sub-step 3 (set 1)
             mfma_item(1, n);
             if (NEXT.value) lfrag_item(1, 0, 0, n);
-            if (DMA_A.value && (n & 1)) dma_item(k_next + kTK, other_off ^ kStageBytes, n >> 1);
+            if (LOAD_A.value && (n & 1)) dma_a(k0 + 2 * kTK, a_own, n >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (NEXT.value) {
@@ -1099,38 +1107,35 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
             lfrag_item(1, 0, 0, 9);
         }
         __builtin_amdgcn_sched_barrier(0);
-        // point the address registers at the other stage
+        // advance to the next step's stages
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) a_addr[i][ks] ^= kStageBytes;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) b_addr[j] ^= kStageBytes;
+        for (int j = 0; j < 4; ++j) b_addr[j] += b_next_delta;
+        a_own ^= kStageBytes;
+        b_own = b_own == 2 * kStageBytes ? 0 : b_own + kStageBytes;
+        b_next_delta = b_own == 2 * kStageBytes ? -2 * kStageBytes : kStageBytes;
     };
     using Yes = std::integral_constant<bool, true>;
     using No = std::integral_constant<bool, false>;
 
+    // prologue: A of steps 0 and 1, B of steps 0 and 1 (B of step 2 is issued by step 0)
 #pragma unroll
-    for (int n = 0; n < 8; ++n) dma_item(0, 0, n);
+    for (int n = 0; n < 4; ++n) { dma_a(0, 0, n); dma_b(0, 0, n); }
     if (n_steps > 1) {
 #pragma unroll
-        for (int n = 0; n < 4; ++n) dma_item(kTK, kStageBytes, n);
+        for (int n = 0; n < 4; ++n) { dma_a(kTK, kStageBytes, n); dma_b(kTK, kStageBytes, n); }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 #pragma unroll
     for (int n = 0; n < 10; ++n) lfrag_item(0, 0, 0, n);
-    int other_off = kStageBytes;
     uint32_t s = 0;
-    for (; s + 2 < n_steps; ++s) {
-        step(other_off, (s + 1) * kTK, Yes{}, Yes{}, Yes{});
-        other_off ^= kStageBytes;
-    }
-    if (s + 1 < n_steps) {
-        step(other_off, (s + 1) * kTK, Yes{}, No{}, Yes{});
-        other_off ^= kStageBytes;
-    }
-    step(other_off, 0, No{}, No{}, No{});
+    for (; s + 2 < n_steps; ++s) step(s * kTK, Yes{}, Yes{}, Yes{});
+    if (s + 1 < n_steps) step(s * kTK, No{}, No{}, Yes{});
+    step(0, No{}, No{}, No{});
 
     // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4;
     // fragment j of this wavefront holds tile columns 128 wn + 32 j + q (MODE 2) or, in MODE 1,
@@ -1255,10 +1260,10 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
             if (e != hipSuccess) return e;
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<1>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
             if (e != hipSuccess) return e;
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<2>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 131072);
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
             if (e != hipSuccess) return e;
             attr_set = true;
         }
@@ -1268,12 +1273,12 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
             const uint32_t supers = (n_sm * n_sn + 7) / 8 * 8;      // whole rounds over the 8 XCDs
             return dim3(supers * kSuperM * kSuperN, 1, 1);
         };
-        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), 131072, stream, a);
+        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), 163840, stream, a);
         else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<1>, grid_for((a.F + 127) / 128), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), lds_bytes, stream, a);
         mark(2, 0);
         mark(3, 1);
-        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), 131072, stream, a);
+        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), 163840, stream, a);
         else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<2>, grid_for((a.H + 255) / 256), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), lds_bytes, stream, a);
         mark(3, 0);
