@@ -992,9 +992,12 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     // (it cannot see that they go to the other stage), which serialises the whole step.  Here the
     // only wait is the explicit vmcnt(0) before the step's barrier.
     const uint32_t lds_base = uint32_t(uintptr_t((__attribute__((address_space(3))) void*)lds));
+    // (M0 carries the LDS destination and is read when the instruction issues; it is a register the
+    // compiler reserves, so its previous value is put back.)
     auto dma16 = [&](const uint8_t* gptr, uint32_t lds_addr) __attribute__((always_inline)) {
-        asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                     :: "v"(gptr), "s"(lds_addr) : "memory", "m0");
+        uint32_t saved_m0;
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off\n\ts_mov_b32 m0, %0"
+                     : "=&s"(saved_m0) : "v"(gptr), "s"(lds_addr) : "memory");
     };
     // a_stage_off / b_stage_off: byte offset of the destination stage inside the operand's region, uniform
     auto dma_a = [&](uint32_t k0, int a_stage_off, int n) __attribute__((always_inline)) {
@@ -1140,23 +1143,39 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4;
     // fragment j of this wavefront holds tile columns 128 wn + 32 j + q (MODE 2) or, in MODE 1,
     // gate (j = 0, 1) and up (j = 2, 3) of h columns 64 wn + 32 (j & 1) + q
+    if (MODE == 1) {
+        // a lane holds one h column; neighbouring lanes swap values (DPP) so that even lanes store
+        // columns (q, q + 1) of an even row and odd lanes columns (q - 1, q) of the next row: 4-byte
+        // stores instead of 2-byte ones
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int32_t row = wm * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-            if (row >= t.rows) continue;
-            if (MODE == 1) {
+            for (int r = 0; r < 16; r += 2) {
+                const int32_t row = wm * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3) + (q & 1);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    const uint32_t col = n_base + 64u * wn + 32u * j + q;
-                    if (col >= N) continue;
-                    const float ga_ = acc[i][j][r];
-                    const float up = acc[i][j + 2][r];
-                    const float hv = ga_ / (1.0f + __expf(-ga_)) * up;
-                    a.hbuf[size_t(t.row0 + row) * a.F + col] = uint16_t(f32_to_bf16_rne(hv));
+                    uint32_t hb[2];
+#pragma unroll
+                    for (int d = 0; d < 2; ++d) {
+                        const float ga_ = acc[i][j][r + d];
+                        const float up = acc[i][j + 2][r + d];
+                        hb[d] = f32_to_bf16_rne(ga_ / (1.0f + __expf(-ga_)) * up);
+                    }
+                    const uint32_t p0 = uint32_t(__builtin_amdgcn_update_dpp(0, int(hb[0]), 0xB1, 0xF, 0xF, true));
+                    const uint32_t p1 = uint32_t(__builtin_amdgcn_update_dpp(0, int(hb[1]), 0xB1, 0xF, 0xF, true));
+                    const uint32_t packed = (q & 1) ? (p1 | (hb[1] << 16)) : (hb[0] | (p0 << 16));
+                    const uint32_t col = n_base + 64u * wn + 32u * j + (q & ~1);
+                    if (row < t.rows && col < N)
+                        *reinterpret_cast<uint32_t*>(a.hbuf + size_t(t.row0 + row) * a.F + col) = packed;
                 }
-            } else {
+            }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int32_t row = wm * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                if (row >= t.rows) continue;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t col = n_base + 128u * wn + 32u * j + q;
@@ -1164,7 +1183,7 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
                     a.ybuf[size_t(t.row0 + row) * a.H + col] = acc[i][j][r];
                 }
             }
-        }
+    }
 }
 
 // out[t][:] (+)= sum_k gate * sum_split y
