@@ -82,6 +82,7 @@ def test_shapes(kw):
 @pytest.mark.parametrize("kw", [
     dict(tokens=700, top_k=2, n_experts=3, n_slots=3, hidden=192, ffn=320),
     dict(tokens=600, top_k=1, n_experts=2, n_slots=2, hidden=256, ffn=576),
+    dict(tokens=600, top_k=1, n_experts=2, n_slots=2, hidden=64, ffn=128),    # one and two k steps, tile wider than N
 ])
 def test_variants_of_the_tiled_kernels(monkeypatch, kw):
     """FLUXMOE_FFN_TILED_WAVES selects the variant of the LDS-tiled kernels: 2 (default) loads both
