@@ -97,7 +97,7 @@ struct fluxmoe_ctx {
     bool half_done_valid[2] = {false, false};
     // launch shape of the decode kernel (FLUXMOE_DECODE_WAVES / FLUXMOE_DECODE_WG_PER_CU override)
     int tune_waves = 8;
-    int tune_wg_per_cu = 16;
+    int tune_wg_per_cu = 64;
     int tune_chunk = 1;
     int tune_tiled_waves = 2;             // FLUXMOE_FFN_TILED_WAVES: 2 = LDS-direct loads (default), 8 = register-staged,
                                           // 4 = register-staged with four wavefronts of 128 x 128
@@ -278,7 +278,7 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     }
     if (const char* v = std::getenv("FLUXMOE_DECODE_WG_PER_CU")) {
         const int w = std::atoi(v);
-        if (w >= 1 && w <= 64) c->tune_wg_per_cu = w;
+        if (w >= 1 && w <= 1024) c->tune_wg_per_cu = w;
     }
     if (const char* v = std::getenv("FLUXMOE_FFN_TILED_WAVES")) {
         const int w = std::atoi(v);
