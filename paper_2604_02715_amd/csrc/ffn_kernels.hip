@@ -123,6 +123,13 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
     }
 }
 
+// SiLU(g) * u (Sec. 2.1's gated FFN) in FP32 with the hardware's exp2 and reciprocal, each within one
+// ulp; the caller rounds the product to BF16.  g -> -inf gives exp2 = +inf, reciprocal 0, product -0.
+__device__ __forceinline__ float swiglu(float g, float u) {
+    const float e = __builtin_amdgcn_exp2f(-1.4426950408889634f * g);
+    return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
+}
+
 // ------------------------------------------------------------------ strip GEMM core
 __device__ __forceinline__ uint32_t comp(const uint4& v, int i) {
     return i == 0 ? v.x : (i == 1 ? v.y : (i == 2 ? v.z : v.w));
@@ -394,7 +401,7 @@ __device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileIn
             for (int c = 0; c < 8; ++c) {
                 const float ga = g.acc[mi][c][r];
                 const float up = xch[pair * (MI * 32) + (mi * 8 + c) * 4 + r][lane];
-                const float h = ga / (1.0f + __expf(-ga)) * up;
+                const float h = swiglu(ga, up);
                 hb[c] = f32_to_bf16_rne(h);
             }
             uint4 o;
@@ -695,7 +702,7 @@ __global__ __launch_bounds__(512) void gemm_tiled_kernel(FfnArgs a) {
                 for (int j = 0; j < 2; ++j) {
                     const float ga_ = acc[i][j][r];
                     const float up = acc[i][j + 2][r];
-                    const float h = ga_ / (1.0f + __expf(-ga_)) * up;
+                    const float h = swiglu(ga_, up);
                     packed |= f32_to_bf16_rne(h) << (16 * j);
                 }
                 *reinterpret_cast<uint32_t*>(a.hbuf + size_t(t.row0 + row) * a.F + col) = packed;
@@ -903,7 +910,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 for (int j = 0; j < 2; ++j) {
                     const float ga_ = acc[i][j][r];
                     const float up = acc[i][j + 2][r];
-                    const float h = ga_ / (1.0f + __expf(-ga_)) * up;
+                    const float h = swiglu(ga_, up);
                     packed |= f32_to_bf16_rne(h) << (16 * j);
                 }
                 *reinterpret_cast<uint32_t*>(a.hbuf + size_t(t.row0 + row) * a.F + col) = packed;
@@ -941,8 +948,12 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     const uint32_t n_ct = (N + ncols_tile - 1) / ncols_tile;
     const uint32_t n_rt = uint32_t(a.n_tiles[0]);
     const uint32_t n_sn = (n_ct + kSuperN - 1) / kSuperN;
+    // Workgroups go to the 8 XCDs round robin, so (super-tile, K split) pair number p runs on XCD
+    // p % 8: the splits of one super-tile land on different XCDs
+    const uint32_t n_split = MODE == 2 ? a.ksplit : 1u;
     const uint32_t xcd = blockIdx.x % 8u, jj = blockIdx.x / 8u;
-    const uint32_t st = (jj / (kSuperM * kSuperN)) * 8u + xcd;
+    const uint32_t pair = (jj / (kSuperM * kSuperN)) * 8u + xcd;
+    const uint32_t st = pair / n_split, split = pair % n_split;
     const uint32_t within = jj % (kSuperM * kSuperN);
     const uint32_t row_tile = (st / n_sn) * kSuperM + within / kSuperN;
     const uint32_t col_tile = (st % n_sn) * kSuperN + within % kSuperN;
@@ -950,6 +961,13 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     TileInfo t;
     if (!tile_info(a, row_tile, t)) return;
     const uint32_t n_base = col_tile * ncols_tile;
+
+    // split K (second product only): this workgroup multiplies steps [step_lo, step_hi) of the K / 64
+    // and writes its own FP32 partial, which combine_kernel sums in split order
+    const uint32_t n_steps_all = K / kTK;
+    const uint32_t step_lo = uint32_t(uint64_t(n_steps_all) * split / n_split);
+    const uint32_t step_hi = uint32_t(uint64_t(n_steps_all) * (split + 1) / n_split);
+    const uint32_t k_begin = step_lo * kTK;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -960,7 +978,7 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
 
     // ---- global sources of this lane's LDS-direct loads (4 for A, 4 for B per step): 32-bit byte
     // offsets from bases that are uniform over the workgroup
-    const uint8_t* const a_base = reinterpret_cast<const uint8_t*>(MODE == 1 ? a.tokens : a.hbuf);
+    const uint8_t* const a_base = reinterpret_cast<const uint8_t*>(MODE == 1 ? a.tokens : a.hbuf) + size_t(k_begin) * 2;
     uint32_t a_off[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -974,7 +992,7 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     }
     const size_t mat = size_t(a.H) * a.F;
     const uint8_t* const b_base = reinterpret_cast<const uint8_t*>(
-        MODE == 1 ? a.slots13 + size_t(t.slot) * 2 * mat : a.slots2 + size_t(t.slot) * mat);
+        MODE == 1 ? a.slots13 + size_t(t.slot) * 2 * mat : a.slots2 + size_t(t.slot) * mat + size_t(k_begin) * N);
     uint32_t b_off[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -1056,7 +1074,7 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], __builtin_bit_cast(bf16x8, full), acc[i][j], 0, 0, 0);
     };
 
-    const uint32_t n_steps = K / kTK;
+    const uint32_t n_steps = step_hi - step_lo;                // >= 1: the host keeps ksplit <= K / 64
     // Step s multiplies A stage s % 2 and B stage s % 3.  After its barrier nobody reads those
     // stages any more, so sub-step 3 issues the A loads of step s + 2 into the same A stage and
     // sub-step 0 of the next step issues the B loads of step s + 3 into the same B stage: B, whose
@@ -1159,7 +1177,7 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
                     for (int d = 0; d < 2; ++d) {
                         const float ga_ = acc[i][j][r + d];
                         const float up = acc[i][j + 2][r + d];
-                        hb[d] = f32_to_bf16_rne(ga_ / (1.0f + __expf(-ga_)) * up);
+                        hb[d] = f32_to_bf16_rne(swiglu(ga_, up));
                     }
                     const uint32_t p0 = uint32_t(__builtin_amdgcn_update_dpp(0, int(hb[0]), 0xB1, 0xF, 0xF, true));
                     const uint32_t p1 = uint32_t(__builtin_amdgcn_update_dpp(0, int(hb[1]), 0xB1, 0xF, 0xF, true));
@@ -1180,7 +1198,7 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
                 for (int j = 0; j < 4; ++j) {
                     const uint32_t col = n_base + 128u * wn + 32u * j + q;
                     if (col >= N) continue;
-                    a.ybuf[size_t(t.row0 + row) * a.H + col] = acc[i][j][r];
+                    a.ybuf[(size_t(split) * a.pairs_cap + size_t(t.row0 + row)) * a.H + col] = acc[i][j][r];
                 }
             }
     }
@@ -1264,6 +1282,8 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
         const size_t lds_bytes = 4 * size_t(kTM) * kLdsPitch * sizeof(uint16_t);
         const bool four = a.tiled_waves == 4;
         const bool d2l = a.tiled_waves == 2;
+        if (!d2l && a.ksplit != 1) return hipErrorInvalidValue;     // only the LDS-direct kernel splits K
+        if (a.ksplit == 0 || a.ksplit > a.F / kTK) return hipErrorInvalidValue;
         static bool attr_set = false;
         if (!attr_set) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled_kernel<1>),
@@ -1287,9 +1307,9 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
             attr_set = true;
         }
         mark(2, 1);
-        auto grid_for = [&](uint32_t n_ct) {
+        auto grid_for = [&](uint32_t n_ct, uint32_t n_split = 1) {
             const uint32_t n_sm = (a.tiles_cap + kSuperM - 1) / kSuperM, n_sn = (n_ct + kSuperN - 1) / kSuperN;
-            const uint32_t supers = (n_sm * n_sn + 7) / 8 * 8;      // whole rounds over the 8 XCDs
+            const uint32_t supers = (n_sm * n_sn * n_split + 7) / 8 * 8;      // whole rounds over the 8 XCDs
             return dim3(supers * kSuperM * kSuperN, 1, 1);
         };
         if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), 163840, stream, a);
@@ -1297,7 +1317,7 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
         else hipLaunchKernelGGL(gemm_tiled_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), lds_bytes, stream, a);
         mark(2, 0);
         mark(3, 1);
-        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), 163840, stream, a);
+        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<2>, grid_for((a.H + 255) / 256, a.ksplit), dim3(512), 163840, stream, a);
         else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<2>, grid_for((a.H + 255) / 256), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), lds_bytes, stream, a);
         mark(3, 0);

@@ -149,7 +149,19 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
     ks = std::min<uint64_t>(ks, 8);
     ks = std::min<uint64_t>(ks, std::max<uint64_t>(1, F / 256));
     p.ksplit = uint32_t(std::max<uint64_t>(ks, 1));
-    if (p.m_tile == 256) p.ksplit = 1;
+    if (p.m_tile == 256) {
+        // LDS-tiled kernels: one 256 x 256 tile per workgroup.  When the second product has fewer tiles
+        // than the chip has CUs, the LDS-direct kernel splits K so that about one workgroup per CU runs
+        // (each split keeps at least 8 steps of 64)
+        p.ksplit = 1;
+        if (c->tune_tiled_waves == 2) {
+            const uint64_t tiles2 = groups * ((avg + 255) / 256) * ((H + 255) / 256);
+            uint64_t k2 = std::max<uint64_t>(1, uint64_t(std::max(c->n_cus, 1)) / tiles2);
+            k2 = std::min<uint64_t>(k2, 8);
+            k2 = std::min<uint64_t>(k2, std::max<uint64_t>(1, F / 512));
+            p.ksplit = uint32_t(k2);
+        }
+    }
     uint64_t o = 0;
     auto take = [&](uint64_t bytes) { uint64_t at = o; o = align_up(o + bytes, 256); return at; };
     p.off_count = take((E + 1) * 4);

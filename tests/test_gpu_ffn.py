@@ -74,6 +74,9 @@ def test_c1_tiny():
     dict(tokens=16, top_k=8, hidden=256, ffn=4096),            # K split of the second product
     dict(tokens=700, top_k=2, n_experts=3, n_slots=3, hidden=192, ffn=320),   # LDS-tiled path, ragged edges
     dict(tokens=520, top_k=1, n_experts=2, n_slots=2, hidden=256, ffn=512),   # LDS-tiled path, full tiles + tail rows
+    dict(tokens=300, top_k=1, n_experts=2, n_slots=2, hidden=256, ffn=1600),  # LDS-tiled path, K of the second product
+                                                                              # split three ways (8, 8, 9 steps)
+    dict(tokens=300, top_k=1, n_experts=2, n_slots=2, hidden=320, ffn=4096),  # split eight ways, ragged column tile
 ])
 def test_shapes(kw):
     run_ffn_case(inputs.scaled(inputs.CONFIGS["c1_tiny"], **kw), seed=1)
