@@ -144,18 +144,41 @@ template <int MI> struct SmallerBody { static constexpr int value = MI == 6 ? 4 
 // kABlock k values of the tile's rows is loaded once per workgroup into LDS (two buffers) instead of
 // once per wavefront from L2 (where it costs 0.75 bytes of requests per weight byte streamed).
 constexpr int kABlock = 128;                 // k per block = 4 chunks
-constexpr int kAPitch = kABlock + 8;         // LDS row pitch in elements (272 bytes: conflict-free 16-byte reads)
+
+// acc += a * b (v_mfma_f32_16x16x32_bf16) with the accumulator pinned to the AGPR half of the register
+// file.  Written as assembly because with the builtin the register allocator, short of VGPRs for
+// 192 accumulators plus the load ring, parks ring registers in AGPRs and moves them back (more
+// v_accvgpr moves than MFMAs in the ring loop).  The matrix-core hazards the compiler would cover
+// are covered here: s_nop 1 gives the two wait states between a VALU write of an operand (the
+// v_perm transposes, the v_accvgpr_write zeroing) and the MFMA that reads it; mfma_drain() must
+// run before anything but another mfma16 reads an accumulator.  volatile keeps the statements in
+// program order (loads and LDS reads stay where the source puts them relative to the MFMAs).
+__device__ __forceinline__ void mfma16(f32x4& acc, const bf16x8& a, const bf16x8& b) {
+    asm volatile("s_nop 1\n\tv_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// 2 x 16 wait states: more than the 18 the longest matrix instruction needs before its result may
+// be read by a vector, memory or LDS instruction
+__device__ __forceinline__ void mfma_drain() {
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+}
 
 // One wavefront's product C[16*MI rows][128 columns] = A[rows][k range] * B[k range][strip].
 template <int MI>
 struct StripGemm {
     f32x4 acc[MI][8];
 
-    static constexpr int kABufElems = 16 * MI * kAPitch;     // one LDS buffer
+    static constexpr int kABufElems = 16 * MI * kABlock;     // one LDS buffer (rows of 256 bytes)
 
-    __device__ __forceinline__ static void load_b(uint4 (&b)[8], const uint16_t* bcol, size_t ldb, uint32_t k0) {
+    // B rows come through buffer loads: one descriptor per expert matrix (scalar registers), one
+    // VGPR with the lane's byte offset inside a chunk, and the row's byte offset as the scalar
+    // offset operand - no vector arithmetic per load.  row0_bytes: offset of the chunk's first row.
+    __device__ __forceinline__ static void load_b(uint4 (&b)[8], __amdgpu_buffer_rsrc_t rsrc, uint32_t voff,
+                                                  uint32_t row0_bytes, uint32_t row_bytes) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) b[r] = *reinterpret_cast<const uint4*>(bcol + size_t(k0 + r) * ldb);
+        for (int r = 0; r < 8; ++r) {
+            const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, row0_bytes + uint32_t(r) * row_bytes, 0);
+            b[r] = make_uint4(v.x, v.y, v.z, v.w);
+        }
     }
 
     __device__ __forceinline__ void mma_b(const uint4 (&b)[8], const uint4 (&a)[MI]) {
@@ -171,62 +194,82 @@ struct StripGemm {
             for (int mi = 0; mi < MI; ++mi) {
                 Frag fa;
                 fa.u = a[mi];
-                acc[mi][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v, f.v, acc[mi][c], 0, 0, 0);
+                mfma16(acc[mi][c], fa.v, f.v);
             }
         }
     }
 
     // The first n_blocks * kABlock k values of the range with A shared through LDS.  Every wavefront
-    // of the workgroup must call this with the same arow_ld, k_begin and n_blocks (it contains
-    // barriers).  arow_ld[i] points at row 16 i + tid / 16 of the tile (clamped to the last row),
-    // already advanced by 8 (tid % 16) elements: the thread's 16-byte piece of each block row.
-    // B runs through a four-deep register ring as in run().
-    __device__ __forceinline__ void run_shared(const uint16_t* const (&arow_ld)[MI], uint16_t* abuf,
-                                               const uint16_t* bcol, size_t ldb, uint32_t k_begin,
-                                               uint32_t n_blocks, int lane, int tid) {
+    // of the four in the workgroup must call this with the same abase, k_begin and n_blocks (it
+    // contains barriers).
+    // A: a block is 16 MI rows x 128 k; it goes from global memory straight into LDS
+    // (global_load_lds_dwordx4: no registers, no LDS write instructions), one instruction per
+    // wavefront per 16 rows: lane (tid / 16, tid % 16) brings one 16-byte piece of row 16 i + tid / 16.
+    // Such a load fills 1 KiB contiguously, so rows are 256 bytes apart with no padding; to keep the
+    // 16-byte fragment reads of 16 consecutive rows on different banks, position p of row r holds
+    // piece p ^ (r % 16).  abase is uniform over the workgroup; aoff[i] is the thread's byte offset of
+    // piece (tid % 16) ^ (tid / 16 % 16) of row 16 i + tid / 16 (clamped to the tile's last row).
+    // B: bmat points at the [k_rows][ldb] matrix (uniform over the wavefront, under 4 GiB), col is the
+    // lane's first column; a four-deep register ring as in run().
+    __device__ __forceinline__ void run_shared(const uint8_t* abase, const uint32_t (&aoff)[MI], uint16_t* abuf,
+                                               const uint16_t* bmat, uint32_t k_rows, uint32_t col, uint32_t ldb,
+                                               uint32_t k_begin, uint32_t n_blocks, int lane, int wave) {
         if (n_blocks == 0) return;
         const uint32_t kg = 8u * (uint32_t(lane) >> 4);
-        const uint32_t kb = k_begin + kg;
-        const int a_st = (tid >> 4) * kAPitch + 8 * (tid & 15);                 // + 16 i rows
-        const int a_fr = (lane & 15) * kAPitch + int(kg);                       // + 16 mi rows, + 32 c
-        uint4 areg[MI];
+        const uint32_t row_bytes = 2u * ldb;
+        // descriptor word 3 = 0x00020000: raw 32-bit data format of this architecture family
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(bmat), 0, int(k_rows * row_bytes), 0x00020000);
+        const uint32_t voff = kg * row_bytes + 2u * col;
+        const uint32_t first_bytes = k_begin * row_bytes;
+        const uint32_t chunk_bytes = uint32_t(kChunk) * row_bytes;
+        // fragment of chunk c, tile mi: row 16 mi + lane % 16, piece 4 c + lane / 16
+        const int a_fr = (lane & 15) * (2 * kABlock) + 16 * ((lane >> 4) ^ (lane & 15));   // bytes; ^ 64 c, + 4096 mi
+        const uint8_t* const abuf8 = reinterpret_cast<const uint8_t*>(abuf);
+        const uint32_t abuf_lds = uint32_t(uintptr_t((__attribute__((address_space(3))) void*)abuf));
         uint4 bst[4][8];
-        auto a_load = [&](uint32_t blk) __attribute__((always_inline)) {
+        // M0 carries the LDS destination of an LDS-direct load and is read when the instruction
+        // issues; the compiler reserves it, so its value is put back
+        auto a_dma = [&](uint32_t blk, uint32_t buf_bytes) __attribute__((always_inline)) {
+            const uint8_t* src = abase + (size_t(k_begin) + size_t(blk) * kABlock) * 2;
 #pragma unroll
-            for (int i = 0; i < MI; ++i) areg[i] = *reinterpret_cast<const uint4*>(arow_ld[i] + k_begin + blk * kABlock);
+            for (int i = 0; i < MI; ++i) {
+                uint32_t saved_m0;
+                const uint32_t dst = abuf_lds + buf_bytes + uint32_t(i * 4 + wave) * 1024u;
+                asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2\n\ts_mov_b32 m0, %0"
+                             : "=&s"(saved_m0) : "v"(aoff[i]), "s"(src), "s"(dst) : "memory");
+            }
         };
-        auto a_store = [&](uint16_t* buf) __attribute__((always_inline)) {
-#pragma unroll
-            for (int i = 0; i < MI; ++i) *reinterpret_cast<uint4*>(buf + a_st + 16 * i * kAPitch) = areg[i];
-        };
+        constexpr uint32_t kBufBytes = uint32_t(kABufElems) * 2;
         // one block of four chunks; PREFETCH: all four B loads three chunks ahead are inside the
         // shared range and the next A block exists
-        auto block = [&](const uint16_t* cur, uint16_t* nxt, uint32_t blk, auto PREFETCH) __attribute__((always_inline)) {
-            if (PREFETCH.value) a_load(blk + 1);
+        auto block = [&](uint32_t cur_bytes, uint32_t nxt_bytes, uint32_t blk, auto PREFETCH) __attribute__((always_inline)) {
+            if (PREFETCH.value) a_dma(blk + 1, nxt_bytes);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const uint32_t chunk = blk * 4 + c;
-                if (PREFETCH.value || chunk + 3 < n_blocks * 4) load_b(bst[(c + 3) & 3], bcol, ldb, kb + (chunk + 3) * kChunk);
+                if (PREFETCH.value || chunk + 3 < n_blocks * 4) load_b(bst[(c + 3) & 3], rsrc, voff, first_bytes + (chunk + 3) * chunk_bytes, row_bytes);
                 uint4 af[MI];
 #pragma unroll
                 for (int mi = 0; mi < MI; ++mi)
-                    af[mi] = *reinterpret_cast<const uint4*>(cur + a_fr + 16 * mi * kAPitch + 32 * c);
+                    af[mi] = *reinterpret_cast<const uint4*>(abuf8 + cur_bytes + ((a_fr ^ (64 * c)) + 4096 * mi));
                 mma_b(bst[c], af);
             }
-            if (PREFETCH.value) a_store(nxt);
+            // the A block fetched above was issued before this block's 32 B loads and loads return in
+            // order: at most the 24 newest (three chunks of B) may still be in flight
+            if (PREFETCH.value) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
             __syncthreads();
         };
-        a_load(0);
+        a_dma(0, 0);
 #pragma unroll
-        for (int c = 0; c < 3; ++c) load_b(bst[c], bcol, ldb, kb + c * kChunk);
-        a_store(abuf);
+        for (int c = 0; c < 3; ++c) load_b(bst[c], rsrc, voff, first_bytes + uint32_t(c) * chunk_bytes, row_bytes);
+        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
         __syncthreads();
         uint32_t blk = 0;
         for (; blk + 1 < n_blocks; ++blk)
-            block(abuf + (blk & 1) * kABufElems, abuf + ((blk + 1) & 1) * kABufElems, blk,
-                  std::integral_constant<bool, true>{});
-        block(abuf + (blk & 1) * kABufElems, abuf + ((blk + 1) & 1) * kABufElems, blk,
-              std::integral_constant<bool, false>{});
+            block((blk & 1) * kBufBytes, ((blk + 1) & 1) * kBufBytes, blk, std::integral_constant<bool, true>{});
+        block((blk & 1) * kBufBytes, ((blk + 1) & 1) * kBufBytes, blk, std::integral_constant<bool, false>{});
+        mfma_drain();
     }
 
     struct Stage {
@@ -262,7 +305,7 @@ struct StripGemm {
             for (int mi = 0; mi < MI; ++mi) {
                 Frag fa;
                 fa.u = st.a[mi];
-                acc[mi][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa.v, f.v, acc[mi][c], 0, 0, 0);
+                mfma16(acc[mi][c], fa.v, f.v);
             }
         }
     }
@@ -317,6 +360,7 @@ struct StripGemm {
             if (k_full + kg < k_end) load(t, arow, bcol, ldb, k_full + kg);
             mma(t);
         }
+        mfma_drain();
     }
 };
 
@@ -348,7 +392,7 @@ __device__ __forceinline__ bool tile_info(const FfnArgs& a, uint32_t tile, TileI
 template <int MI>
 __device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileInfo& t, float (*xch)[64], uint16_t* abuf) {
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));   // uniform: scalar address arithmetic
     const int pair = wave >> 1;
     const int mat_id = wave & 1;
     const uint32_t strip = blockIdx.x * 2 + pair;
@@ -366,18 +410,19 @@ __device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileIn
     const size_t mat = size_t(a.H) * a.F;
     const uint16_t* w = a.slots13 + size_t(t.slot) * 2 * mat + size_t(mat_id) * mat;
 
-    // the loader's rows of the shared A blocks: row 16 i + tid / 16, piece tid % 16
-    const uint16_t* arow_ld[MI];
+    // the thread's pieces of the shared A blocks: row 16 i + tid / 16, piece (tid % 16) ^ (tid / 16 % 16)
+    const uint32_t piece = (threadIdx.x & 15u) ^ ((threadIdx.x >> 4) & 15u);
+    uint32_t aoff[MI];
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
         const int32_t r = min(i * 16 + int(threadIdx.x >> 4), t.rows - 1);
         const int32_t pr = a.sorted_pair[t.row0 + r];
-        arow_ld[i] = a.tokens + size_t(uint32_t(pr) / a.K) * a.H + 8 * (threadIdx.x & 15);
+        aoff[i] = 2u * ((uint32_t(pr) / a.K) * a.H + 8u * piece);          // the launcher checks T * H * 2 < 4 GiB
     }
     StripGemm<MI> g;
     g.zero();
     const uint32_t n_blocks = a.H / kABlock;
-    g.run_shared(arow_ld, abuf, w + (col_ok ? n0 : a.F - 8), a.F, 0, n_blocks, lane, threadIdx.x);
+    g.run_shared(reinterpret_cast<const uint8_t*>(a.tokens), aoff, abuf, w, a.H, col_ok ? n0 : a.F - 8, a.F, 0, n_blocks, lane, wave);
     g.run(arow, w + (col_ok ? n0 : a.F - 8), a.F, n_blocks * kABlock, a.H, lane);
 
     if (mat_id == 1) {
@@ -431,7 +476,7 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
 template <int MI>
 __device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t, uint16_t* abuf) {
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
     const uint32_t strip = blockIdx.x * 4 + wave;
     const uint32_t n0 = strip * kStrip + 8u * (lane & 15);
     const bool col_ok = n0 < a.H;                 // wavefronts past the last strip still run (barriers below)
@@ -448,16 +493,19 @@ __device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t, 
     }
     const uint16_t* w2 = a.slots2 + size_t(t.slot) * a.F * a.H;
 
-    const uint16_t* arow_ld[MI];
+    // the thread's pieces of the shared A blocks, as byte offsets from the tile's first row of h
+    const uint32_t piece = (threadIdx.x & 15u) ^ ((threadIdx.x >> 4) & 15u);
+    uint32_t aoff[MI];
 #pragma unroll
     for (int i = 0; i < MI; ++i) {
         const int32_t r = min(i * 16 + int(threadIdx.x >> 4), t.rows - 1);
-        arow_ld[i] = a.hbuf + size_t(t.row0 + r) * a.F + 8 * (threadIdx.x & 15);
+        aoff[i] = 2u * (uint32_t(r) * a.F + 8u * piece);
     }
     StripGemm<MI> g;
     g.zero();
     const uint32_t n_blocks = (k_end - k_begin) / kABlock;
-    g.run_shared(arow_ld, abuf, w2 + (col_ok ? n0 : a.H - 8), a.H, k_begin, n_blocks, lane, threadIdx.x);
+    g.run_shared(reinterpret_cast<const uint8_t*>(a.hbuf + size_t(t.row0) * a.F), aoff, abuf, w2, a.F, col_ok ? n0 : a.H - 8, a.H,
+                 k_begin, n_blocks, lane, wave);
     g.run(arow, w2 + (col_ok ? n0 : a.H - 8), a.H, k_begin + n_blocks * kABlock, k_end, lane);
 
     if (!col_ok) return;
@@ -1328,6 +1376,8 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
         return hipGetLastError();
     }
     if (a.m_tile != 16 && a.m_tile != 32 && a.m_tile != 64 && a.m_tile != 96) return hipErrorInvalidValue;
+    // the strip kernels address activations and one expert matrix with 32-bit byte offsets
+    if (uint64_t(a.T) * a.H * 2 >= (1ull << 32) || uint64_t(a.H) * a.F * 2 >= (1ull << 31)) return hipErrorInvalidValue;
     mark(2, 1);
     if (a.m_tile == 16) hipLaunchKernelGGL(gemm1_swiglu_kernel<1>, g1, dim3(256), 0, stream, a);
     else if (a.m_tile == 32) hipLaunchKernelGGL(gemm1_swiglu_kernel<2>, g1, dim3(256), 0, stream, a);

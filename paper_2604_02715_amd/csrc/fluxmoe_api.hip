@@ -141,14 +141,22 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
     }
     p.pairs_cap = uint32_t(std::max<uint64_t>(pairs, 1));
     p.tiles_cap = uint32_t(pairs / p.m_tile + groups + 1);
-    // split K of the second product until about 8 wavefronts per CU have work
+    // Split K of the second product (strip kernels).  One workgroup (four strips, one per SIMD) fits on a
+    // CU at a time, so the launch runs in rounds of n_cus workgroups; the split is the one with the
+    // smallest estimated time in units of k rows per workgroup: rounds x (rows per split + a fixed
+    // start-up cost) + the FP32 partials it writes and combine_kernel reads back.
     const uint64_t strips2 = (H + 127) / 128;
     const uint64_t est_tiles = std::max<uint64_t>(1, std::max<uint64_t>(pairs / p.m_tile, std::min(groups, pairs)));
-    const uint64_t jobs = strips2 * est_tiles;
-    uint64_t ks = (2048 + jobs - 1) / jobs;
-    ks = std::min<uint64_t>(ks, 8);
-    ks = std::min<uint64_t>(ks, std::max<uint64_t>(1, F / 256));
-    p.ksplit = uint32_t(std::max<uint64_t>(ks, 1));
+    const uint64_t n_cus = uint64_t(std::max(c->n_cus, 1));
+    uint64_t ks = 1, best_cost = ~0ull;
+    for (uint64_t k = 1; k <= 8 && k <= std::max<uint64_t>(1, F / 256); ++k) {
+        const uint64_t wgs = (strips2 + 3) / 4 * est_tiles * k;
+        const uint64_t rounds = (wgs + n_cus - 1) / n_cus;
+        const uint64_t partials = k > 1 ? k * pairs * H * 8 / (n_cus * 1024) : 0;
+        const uint64_t cost = rounds * ((F + k - 1) / k + 384) + partials;
+        if (cost < best_cost) { best_cost = cost; ks = k; }
+    }
+    p.ksplit = uint32_t(ks);
     if (p.m_tile == 256) {
         // LDS-tiled kernels: one 256 x 256 tile per workgroup.  When the second product has fewer tiles
         // than the chip has CUs, the LDS-direct kernel splits K so that about one workgroup per CU runs
