@@ -44,7 +44,8 @@ def main():
                          "prefix (the config's block fraction) | hbm | balanced (measured "
                          "beta_cpu / (beta_gpu + beta_cpu), whole down tensors) | budget (--host-budget as "
                          "whole down tensors in every layer) | whole_layer (the last layers entirely on the "
-                         "host, same budget) | all")
+                         "host, same budget) | balanced_raw, budget_raw (the same splits with the host tensors "
+                         "stored as dense BF16 and copied, not decoded) | all (the first five)")
     ap.add_argument("--small", action="store_true",
                     help="c5_stream only: a reduced copy of the config (quick functional run, not a result)")
     ap.add_argument("--host-budget", type=float, default=0.125,
@@ -472,14 +473,19 @@ def bench_streaming(cfg, args):
         if hasattr(torch._C, "_host_emptyCache"):
             torch._C._host_emptyCache()                      # give pinned buffers of the last placement back
         info = {"placement": placement}
+        if placement.endswith("_raw"):
+            info["host_tier_format"] = "dense BF16 (share below is dense host bytes over the compressed pool)"
         host_bytes = []
-        if placement == "balanced":
+        raw = placement.endswith("_raw")                     # host tensors stored dense (tier 2), not compressed
+        if placement in ("balanced", "balanced_raw"):
             beta_gpu, beta_cpu, pcie = measure_betas()
+            if raw:
+                beta_cpu = pcie                              # dense bytes cross PCIe as they are
             x_bw, n_down, n_fused = B.fluxmoe_balanced_split(beta_gpu, beta_cpu, E)
             info.update(beta_gpu_GBps=round(beta_gpu / 1e9, 1), beta_cpu_GBps=round(beta_cpu / 1e9, 1),
                         pcie_GBps=round(pcie / 1e9, 1), x_bw=round(x_bw, 5), host_down_tensors=n_down,
                         host_fused_tensors=n_fused, x_realised=round((n_down + 2 * n_fused) / (3 * E), 5))
-        elif placement == "budget":
+        elif placement in ("budget", "budget_raw"):
             units = math.ceil(3 * E * args.host_budget - 1e-12)
             n_down = min(units, E)
             n_fused = min(E, (units - n_down + 1) // 2)
@@ -492,6 +498,11 @@ def bench_streaming(cfg, args):
             hb = n_host * 4096
             if placement in ("balanced", "budget"):
                 hb = pool.place_tensors_on_host(layer, blobs[layer], host_tensors_of(n_down, n_fused))
+            elif raw:
+                w13, w2 = inputs.layer_weights(cfg, layer, device="cuda")
+                hb = pool.place_tensors_raw_on_host(
+                    layer, [((t, e), (w2[e] if t == 2 else w13[e]).cpu()) for (t, e) in host_tensors_of(n_down, n_fused)])
+                del w13, w2
             host_bytes.append(hb)
         if placement == "whole_layer":
             info.update(host_budget=args.host_budget, host_layers=n_host_layers)
@@ -560,8 +571,9 @@ def bench_streaming(cfg, args):
             if placement in ("prefix", "whole_layer"):
                 fetched = host_bytes[hl] * len(proxy.plan[hl][0]) / E
             else:
-                fetched = sum(B.fluxmoe_tensor_blocks(pool.ctx, hl, t, e)[1] * 4096
-                              for (t, e) in host_tensors_of(n_down, n_fused) if e in set(int(v) for v in proxy.plan[hl][0]))
+                routed = set(int(v) for v in proxy.plan[hl][0])
+                fetched = sum((cfg.sigma2 if t == 2 else cfg.sigma1) if raw else B.fluxmoe_tensor_blocks(pool.ctx, hl, t, e)[1] * 4096
+                              for (t, e) in host_tensors_of(n_down, n_fused) if e in routed)
             pcie_rate = round(fetched / (copy_ms * 1e-3) / 1e9, 1)
         union = np.mean([len(u) for u, _ in proxy.plan])
         dense_bytes = union * (cfg.sigma1 + cfg.sigma2)

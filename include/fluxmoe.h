@@ -153,14 +153,25 @@ int fluxmoe_bind_layer(fluxmoe_ctx* ctx, uint32_t layer, const void* hbm_blocks,
  * Move one whole tensor of a bound layer to another backing copy (Sec. 4.3 "Runtime
  * adaptation": tensor-level offloading and restoration between compressed GPU memory and
  * pinned host memory, inside a running engine).  From this call on fluxmoe_materialize reads
- * the type-`type` tensor of `expert` from `blocks`: tier 1 = pinned host memory (fetched by
- * DMA into the staging buffer first), tier 0 = device memory.  `blocks` holds the tensor's
- * blocks exactly as fluxmoe_encode_pool wrote them (fluxmoe_tensor_blocks gives their range in
- * the layer blob), 16-byte aligned.  Host state only, nothing is enqueued: work enqueued
+ * the type-`type` tensor of `expert` from `blocks`:
+ *   FLUXMOE_TIER_HBM       device memory, the tensor's compressed blocks;
+ *   FLUXMOE_TIER_HOST      pinned host memory, the tensor's compressed blocks (fetched by DMA into
+ *                          the staging buffer, then decoded like device-resident ones);
+ *   FLUXMOE_TIER_HOST_RAW  pinned host memory, the tensor's dense BF16 bytes (the CPU offload
+ *                          backend as Sec. 4.2 states it: weights in pinned host memory, moved by
+ *                          asynchronous DMA).  Fetched into the staging buffer like the
+ *                          compressed host tier and copied from there into the slot; nothing is
+ *                          decoded.  The staging buffer must hold the dense bytes.
+ * For the first two, `blocks` holds the tensor's blocks exactly as fluxmoe_encode_pool wrote them
+ * (fluxmoe_tensor_blocks gives their range in the layer blob).  16-byte aligned in every case.
+ * Host state only, nothing is enqueued: work enqueued
  * earlier still reads the previous copy, which the caller may free once that work has
  * completed (Sec. 4.3: the retired copy is freed after the events complete).  A host-tier
  * fetch of this layer issued before the call is forgotten.
  */
+#define FLUXMOE_TIER_HBM 0
+#define FLUXMOE_TIER_HOST 1
+#define FLUXMOE_TIER_HOST_RAW 2
 int fluxmoe_set_tensor_backing(fluxmoe_ctx* ctx, uint32_t layer, int type, uint32_t expert,
                                int tier, const void* blocks);
 

@@ -16,6 +16,7 @@ _lib = None
 
 FFN_ACCUMULATE = 1
 FFN_SKIP_UNMAPPED = 2
+TIER_HBM, TIER_HOST, TIER_HOST_RAW = 0, 1, 2
 
 STATUS = {0: "OK", -1: "EINVAL", -2: "ENOMEM", -3: "ECORRUPT", -4: "ERANGE", -5: "EHIP", -6: "ESTATE"}
 

@@ -561,9 +561,10 @@ int fluxmoe_bind_layer(fluxmoe_ctx* c, uint32_t layer, const void* hbm_blocks, u
             const uint64_t a = tm.first_block, b = a + tm.n_blocks();
             const uint64_t hb = std::min(b, std::max(a, n_host_blocks));
             tm.n_host = hb - a;
+            tm.raw_src = nullptr;
             tm.host_src = tm.n_host ? L.host + a * c->d.block_bytes : nullptr;
             tm.hbm_src = hb < b ? L.hbm + (hb - n_host_blocks) * c->d.block_bytes : nullptr;
-            L.host_tensors += tm.n_host ? 1 : 0;
+            L.host_tensors += tm.on_host() ? 1 : 0;
         }
     L.bound = true;
     if (c->half[layer & 1].layer == int64_t(layer)) c->half[layer & 1].layer = -1;
@@ -587,20 +588,22 @@ int fluxmoe_set_tensor_backing(fluxmoe_ctx* c, uint32_t layer, int type, uint32_
     if (!L.bound) return set_error(FLUXMOE_ESTATE, "layer %u is not bound", layer);
     if (type != 1 && type != 2) return set_error(FLUXMOE_EINVAL, "type must be 1 or 2");
     if (expert >= c->d.n_experts) return set_error(FLUXMOE_ERANGE, "expert %u out of range", expert);
-    if (tier != 0 && tier != 1) return set_error(FLUXMOE_EINVAL, "tier must be 0 (HBM) or 1 (pinned host)");
+    if (tier != FLUXMOE_TIER_HBM && tier != FLUXMOE_TIER_HOST && tier != FLUXMOE_TIER_HOST_RAW)
+        return set_error(FLUXMOE_EINVAL, "tier must be 0 (HBM), 1 (pinned host, compressed) or 2 (pinned host, dense)");
     if (!blocks || (uintptr_t(blocks) & 15)) return set_error(FLUXMOE_EINVAL, "blocks must be non-NULL, 16-byte aligned");
     TensorMeta& tm = L.tensors[type - 1][expert];
-    L.host_tensors -= tm.n_host ? 1 : 0;
-    if (tier == 1) {
+    L.host_tensors -= tm.on_host() ? 1 : 0;
+    tm.n_host = 0;
+    tm.host_src = tm.hbm_src = tm.raw_src = nullptr;
+    if (tier == FLUXMOE_TIER_HOST) {
         tm.n_host = tm.n_blocks();
         tm.host_src = static_cast<const uint8_t*>(blocks);
-        tm.hbm_src = nullptr;
+    } else if (tier == FLUXMOE_TIER_HOST_RAW) {
+        tm.raw_src = static_cast<const uint8_t*>(blocks);
     } else {
-        tm.n_host = 0;
-        tm.host_src = nullptr;
         tm.hbm_src = static_cast<const uint8_t*>(blocks);
     }
-    L.host_tensors += tm.n_host ? 1 : 0;
+    L.host_tensors += tm.on_host() ? 1 : 0;
     if (c->half[layer & 1].layer == int64_t(layer)) c->half[layer & 1].layer = -1;   // staged copies are stale
     return FLUXMOE_OK;
 }
@@ -650,12 +653,15 @@ static int stage_host_blocks(fluxmoe_ctx* c, uint32_t layer, const int32_t* ids,
     for (int ti : {1, 0})
         for (int32_t e : sorted) {
             const TensorMeta& tm = L.tensors[ti][e];
-            if (tm.n_host == 0) continue;
+            if (!tm.on_host()) continue;
             st.off[ti][e] = int64_t(cursor);
-            const uint64_t bytes = tm.n_host * B;
-            if (!ranges.empty() && ranges.back().src + ranges.back().bytes == tm.host_src) ranges.back().bytes += bytes;
-            else ranges.push_back({tm.host_src, bytes, cursor});
-            cursor += bytes;
+            // dense tensors are staged whole (a multiple of 16 bytes); the cursor stays block aligned
+            const uint8_t* src = tm.raw_src ? tm.raw_src : tm.host_src;
+            const uint64_t bytes = tm.raw_src ? (ti == 0 ? c->elems13 : c->elems2) * 2 : tm.n_host * B;
+            if (!ranges.empty() && ranges.back().src + ranges.back().bytes == src &&
+                ranges.back().dst + ranges.back().bytes == cursor) ranges.back().bytes += bytes;
+            else ranges.push_back({src, bytes, cursor});
+            cursor += align_up(bytes, B);
         }
     if (cursor > half_bytes)
         return set_error(FLUXMOE_ENOMEM, "staging half holds %llu bytes, layer %u needs %llu",
@@ -700,14 +706,14 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
     bool need_host = false;
     for (uint32_t i = 0; i < n && !need_host; ++i)
         for (int ti = 0; ti < 2; ++ti)
-            if (L.tensors[ti][expert_ids[i]].n_host) need_host = true;
+            if (L.tensors[ti][expert_ids[i]].on_host()) need_host = true;
     bool wait_copy = false;
     if (need_host) {
         StageHalf& st = c->half[layer & 1];
         bool staged = st.layer == int64_t(layer);
         for (uint32_t i = 0; i < n && staged; ++i)
             for (int ti = 0; ti < 2; ++ti)
-                if (L.tensors[ti][expert_ids[i]].n_host && st.off[ti][expert_ids[i]] < 0)
+                if (L.tensors[ti][expert_ids[i]].on_host() && st.off[ti][expert_ids[i]] < 0)
                     staged = false;
         if (!staged) {
             if (int rc = stage_host_blocks(c, layer, expert_ids, n, stream)) return rc;
@@ -729,6 +735,8 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
 
     const int half = layer & 1;
     const uint64_t half_bytes = c->staging ? (c->staging_bytes / 2) / B * B : 0;
+    struct DenseCopy { const uint8_t* src; uint8_t* dst; uint64_t bytes; };
+    std::vector<DenseCopy> dense_copies;     // staged uncompressed tensors: staging -> slot, no decode
     for (int ti = 0; ti < 2; ++ti) {
         DecodeJob* jobs = reinterpret_cast<DecodeJob*>(hcmd + jobs_off[ti]);
         uint32_t nj = 0, blocks = 0;
@@ -738,6 +746,11 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
             const TensorMeta& tm = L.tensors[ti][expert_ids[i]];
             const uint64_t nb = tm.n_blocks(), nh = tm.n_host;     // host part is the first nh blocks
             const uint64_t dst = uint64_t(uintptr_t(arena)) + uint64_t(dst_slots[i]) * sigma;
+            if (tm.raw_src) {
+                dense_copies.push_back({c->staging + half * half_bytes + c->half[half].off[ti][expert_ids[i]],
+                                        reinterpret_cast<uint8_t*>(uintptr_t(dst)), sigma});
+                continue;
+            }
             if (nh) {
                 const uint8_t* src = c->staging + half * half_bytes + c->half[half].off[ti][expert_ids[i]];
                 jobs[nj++] = DecodeJob{uint64_t(uintptr_t(src)), dst, blocks, uint32_t(nh),
@@ -790,6 +803,8 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
     if (wait_copy) HIPCHECK(hipStreamWaitEvent(stream, c->ev_copied[half], 0));
     const size_t used = upd_off + touched.size() * 8;
     HIPCHECK(hipMemcpyAsync(dcmd, hcmd, used, hipMemcpyHostToDevice, stream));
+    for (const DenseCopy& dc : dense_copies)
+        HIPCHECK(hipMemcpyAsync(dc.dst, dc.src, dc.bytes, hipMemcpyDeviceToDevice, stream));
 
     DecodeArgs args{};
     args.cmd = reinterpret_cast<const DecodeCmd*>(dcmd);
@@ -802,6 +817,11 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
     args.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
     const int waves_per_wg = c->tune_waves;
     const uint64_t total = uint64_t(cmd->total_blocks[0]) + cmd->total_blocks[1];
+    if (total == 0) {
+        // every listed tensor is an uncompressed host tensor: nothing to decode, only the page table changes
+        if (!touched.empty())
+            HIPCHECK(launch_apply_updates(page_table, dcmd + upd_off, uint32_t(touched.size()), stream));
+    } else {
     uint32_t n_wg = uint32_t(std::min<uint64_t>(uint64_t(c->n_cus) * c->tune_wg_per_cu, (total + waves_per_wg - 1) / waves_per_wg));
     n_wg = std::max(n_wg, 2u);
     uint32_t split = uint32_t((uint64_t(n_wg) * cmd->total_blocks[1] + total / 2) / total);
@@ -811,6 +831,7 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
     HIPCHECK(span_begin(c, 0, stream));
     HIPCHECK(launch_decode(args, n_wg, waves_per_wg, stream));
     HIPCHECK(span_end(c, stream));
+    }
     HIPCHECK(hipEventRecord(c->ring_ev[slot], stream));
     c->ring_used[slot] = true;
     c->ring_next = (slot + 1) % kRing;

@@ -27,6 +27,10 @@ struct TensorMeta {
     uint64_t n_host = 0;
     const uint8_t* host_src = nullptr;   // pinned address of the tensor's block 0
     const uint8_t* hbm_src = nullptr;    // device address of the tensor's block n_host
+    // uncompressed host backing (the CPU offload backend as Sec. 4.2 states it): pinned address of
+    // the tensor's dense BF16 bytes; when set, n_host = 0 and hbm_src = nullptr
+    const uint8_t* raw_src = nullptr;
+    bool on_host() const { return n_host != 0 || raw_src != nullptr; }
 };
 
 struct LayerMeta {

@@ -115,6 +115,25 @@ class ExpertPool:
         self.host_blobs[layer] = pinned
         return total
 
+    def place_tensors_raw_on_host(self, layer, dense):
+        """Uncompressed host placement (the CPU offload backend as Sec. 4.2 states it): `dense` is a
+        list of ((type, expert), BF16 tensor); the tensors' bytes are packed into one pinned buffer
+        and the library is pointed at them (tier 2: fetched by DMA, copied into the slot, never
+        decoded).  Returns the pinned bytes."""
+        order = sorted(dense, key=lambda kv: (-kv[0][0], kv[0][1]))
+        total = sum(t.numel() * 2 for _, t in order)
+        if total == 0:
+            return 0
+        pinned = torch.empty(total, dtype=torch.uint8, pin_memory=True)
+        at = 0
+        for (t, e), w in order:
+            nbytes = w.numel() * 2
+            pinned[at:at + nbytes].copy_(w.contiguous().reshape(-1).view(torch.uint8))
+            B.fluxmoe_set_tensor_backing(self.ctx, layer, t, e, B.TIER_HOST_RAW, pinned.data_ptr() + at)
+            at += nbytes
+        self.host_blobs[("raw", layer)] = pinned
+        return total
+
     @property
     def cfg_block_bytes(self):
         return 4096

@@ -110,3 +110,55 @@ def test_closed_loop_on_measured_load_times_follows_the_oracle():
     finally:
         B.fluxmoe_planner_destroy(plan)
         pool.close()
+
+
+def test_uncompressed_host_tensors_are_copied_not_decoded():
+    """Tier 2 (Sec. 4.2's CPU offload backend: dense weights in pinned host memory): such tensors
+    reach their slots bit for bit next to compressed host tensors and device-resident ones, with
+    and without an explicit prefetch, and also when nothing at all is left to decode."""
+    from gpu_common import assert_slot_equals
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_layers=2, n_experts=8, n_slots=8)
+    pool, dense, blobs = build(cfg)
+    try:
+        pool.bind_staging(2 * cfg.n_experts * (cfg.sigma1 + cfg.sigma2) + 8192)
+        pool.reset_page_table()
+        w13, w2 = dense[0]
+        raw = [((2, e), w2[e]) for e in (1, 4, 7)] + [((1, e), w13[e]) for e in (0, 4)]
+        assert pool.place_tensors_raw_on_host(0, raw) == 3 * cfg.sigma2 + 2 * cfg.sigma1
+        pool.place_tensors_on_host(0, blobs[0], [(2, 2), (1, 5)])          # compressed host tensors beside them
+        ids = [4, 0, 7, 2, 5, 1, 3]
+        slots = [0, 7, 3, 1, 6, 2, 5]
+        side = torch.cuda.Stream()
+        for prefetch in (False, True):
+            pool.poison_slots()
+            if prefetch:
+                pool.prefetch_host(0, ids, side)
+            pool.materialize(0, ids, slots)
+            torch.cuda.synchronize()
+            assert pool.device_errors() == 0
+            for e, s in zip(ids, slots):
+                assert_slot_equals(pool, s, w13[e], w2[e])
+            table = pool.page_table.cpu().numpy().reshape(cfg.n_layers, cfg.n_experts)
+            assert [table[0, e] for e in ids] == slots and table[0, 6] == -1
+        # the other layer is untouched by the placement and still decodes from device memory
+        check_all_layers(pool, cfg, dense)
+        # every tensor of layer 1 uncompressed on the host: the call only copies and maps
+        w13b, w2b = dense[1]
+        allraw = [((2, e), w2b[e]) for e in range(cfg.n_experts)] + [((1, e), w13b[e]) for e in range(cfg.n_experts)]
+        pool.place_tensors_raw_on_host(1, allraw)
+        pool.poison_slots()
+        order = list(range(cfg.n_experts))
+        pool.materialize(1, order, order[::-1])
+        torch.cuda.synchronize()
+        assert pool.device_errors() == 0
+        for e, s in zip(order, order[::-1]):
+            assert_slot_equals(pool, s, w13b[e], w2b[e])
+        table = pool.page_table.cpu().numpy().reshape(cfg.n_layers, cfg.n_experts)
+        assert list(table[1]) == order[::-1] and (table[0] == -1).all()
+        # back to device-resident compressed blocks
+        for e in range(cfg.n_experts):
+            for t in (1, 2):
+                pool.set_tensor_backing(1, t, e, False, blobs[1])
+        check_all_layers(pool, cfg, dense)
+    finally:
+        pool.close()
