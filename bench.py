@@ -154,7 +154,9 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    B.fluxmoe_profile_enable(pool.ctx, True)
+    # timed region: only the decode kernel (the roofline's kernel) is bracketed by events; an event
+    # between two kernels idles the device for a few microseconds
+    B.fluxmoe_profile_enable(pool.ctx, True, only_kinds=("decode",))
     B.fluxmoe_profile_collect(pool.ctx)
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -162,12 +164,21 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = B.fluxmoe_profile_collect(pool.ctx)
+    # per-kernel breakdown of the FFN: a few more steps, untimed, every kernel bracketed
+    n_break = max(1, min(args.steps, 5))
+    B.fluxmoe_profile_enable(pool.ctx, True)
+    for _ in range(n_break):
+        step()
+    torch.cuda.synchronize()
+    prof_ffn = B.fluxmoe_profile_collect(pool.ctx)
     B.fluxmoe_profile_enable(pool.ctx, False)
     assert pool.device_errors() == 0
+    for k in ("grouping", "gemm1_swiglu", "gemm2", "combine"):
+        prof[k] = prof_ffn[k]
 
     ms_per_step = elapsed / args.steps * 1e3
     decode_ms = prof["decode"][0] / max(1, prof["decode"][1])
-    ffn_ms = sum(prof[k][0] for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")) / args.steps
+    ffn_ms = sum(prof[k][0] for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")) / n_break
     achieved = (comp_bytes + dense_bytes) / (decode_ms * 1e-3) / 1e9
 
     traffic = None

@@ -270,8 +270,12 @@ int fluxmoe_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, 
  * the elapsed milliseconds and launch counts per kind and forgets them:
  *   kind 0 decode + paged scatter, 1 token grouping, 2 gate/up product + SwiGLU,
  *   3 down product, 4 gated combine.
+ * on: 0 = off, 1 = every kind, FLUXMOE_PROFILE_ONLY(mask) = only the kinds whose bit is set in
+ * mask (an event between two kernels costs a few microseconds of idle device time; a benchmark
+ * that times whole steps brackets only the kernel it reports).
  */
 #define FLUXMOE_PROFILE_KINDS 5
+#define FLUXMOE_PROFILE_ONLY(mask) (0x100 | ((mask) & 0x1F))
 int fluxmoe_profile_enable(fluxmoe_ctx* ctx, int on);
 int fluxmoe_profile_collect(fluxmoe_ctx* ctx, double out_ms[FLUXMOE_PROFILE_KINDS],
                             uint32_t out_count[FLUXMOE_PROFILE_KINDS]);

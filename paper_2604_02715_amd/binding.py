@@ -265,8 +265,12 @@ def fluxmoe_mfma_probe(operands_ptr, out_ptr, n_workgroups, iters, stream=None):
 PROFILE_KINDS = ("decode", "grouping", "gemm1_swiglu", "gemm2", "combine")
 
 
-def fluxmoe_profile_enable(ctx, on: bool):
-    _check(lib().fluxmoe_profile_enable(ctx, int(on)))
+def fluxmoe_profile_enable(ctx, on: bool, only_kinds=None):
+    """only_kinds: names from PROFILE_KINDS; None = every kind."""
+    v = int(bool(on))
+    if on and only_kinds is not None:
+        v = 0x100 | sum(1 << PROFILE_KINDS.index(k) for k in only_kinds)
+    _check(lib().fluxmoe_profile_enable(ctx, v))
 
 
 def fluxmoe_profile_collect(ctx) -> dict:

@@ -103,6 +103,8 @@ struct fluxmoe_ctx {
                                           // 4 = register-staged with four wavefronts of 128 x 128
     // optional kernel timing (fluxmoe_profile_*)
     bool profiling = false;
+    uint32_t profile_mask = 0x1F;         // kinds that are bracketed while profiling
+    bool span_open = false;               // the span begun last is being recorded
     struct Span { hipEvent_t a, b; int kind; };
     std::vector<Span> spans;
 };
@@ -234,7 +236,8 @@ int ensure_events(fluxmoe_ctx* c) {
 }
 
 hipError_t span_begin(fluxmoe_ctx* c, int kind, hipStream_t s) {
-    if (!c->profiling) return hipSuccess;
+    c->span_open = c->profiling && ((c->profile_mask >> kind) & 1u);
+    if (!c->span_open) return hipSuccess;
     fluxmoe_ctx::Span sp{nullptr, nullptr, kind};
     hipError_t e = hipEventCreate(&sp.a);
     if (e != hipSuccess) return e;
@@ -245,7 +248,8 @@ hipError_t span_begin(fluxmoe_ctx* c, int kind, hipStream_t s) {
 }
 
 hipError_t span_end(fluxmoe_ctx* c, hipStream_t s) {
-    if (!c->profiling) return hipSuccess;
+    if (!c->span_open) return hipSuccess;
+    c->span_open = false;
     return hipEventRecord(c->spans.back().b, s);
 }
 
@@ -1006,6 +1010,7 @@ int fluxmoe_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, 
 int fluxmoe_profile_enable(fluxmoe_ctx* c, int on) {
     if (!c) return set_error(FLUXMOE_EINVAL, "ctx is NULL");
     c->profiling = on != 0;
+    c->profile_mask = (on & 0x100) ? uint32_t(on & 0x1F) : 0x1Fu;
     return FLUXMOE_OK;
 }
 
