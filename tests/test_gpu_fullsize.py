@@ -121,3 +121,9 @@ def test_c3_qwen3next_shaped_layer_two_waves():
 
 def test_c4_glm45_shaped_layer():
     run_full(inputs.CONFIGS["c4_glm45"])
+
+
+def test_c2_mixtral_shaped_layer_prefill_batch():
+    """The same layer with 1024 tokens (about 256 rows per expert): the LDS-tiled MFMA kernels at
+    full size, the second product with its K split over two workgroups per tile."""
+    run_full(inputs.scaled(inputs.CONFIGS["c2_mixtral"], tokens=1024), n_sample_tokens=2)
