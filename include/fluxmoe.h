@@ -21,7 +21,7 @@
  *   - arguments are validated on the host before anything is enqueued; on error nothing
  *     is enqueued.  Kernels never write outside the bound slot arenas, the page table,
  *     `out` and the bound workspace, whatever the compressed pool contains.
- *   - hidden and ffn must be multiples of 8; block_bytes must be 4096.
+ *   - hidden and ffn must be multiples of 8, hidden * ffn under 2^30; block_bytes must be 4096.
  *
  * Compressed block (block_bytes bytes, independently decodable; this build's container,
  * the paper prints none):
@@ -240,6 +240,9 @@ int fluxmoe_release(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_ids,
  * out_t = sum_k topk_w[t][k] * ( (silu(x_t W1_e) * (x_t W3_e)) W2_e ),  e = topk_ids[t][k];
  * BF16 inputs, FP32 accumulation, the SwiGLU product rounded to BF16 before the second
  * product.  Deterministic (fixed summation order).  T = 0 is valid.
+ * Limits (the kernels address activations and one expert matrix with 32-bit byte offsets):
+ * T <= 65535 and T * hidden * 2 bytes under 4 GiB here (EINVAL, nothing enqueued); hidden * ffn * 2
+ * bytes under 2 GiB is checked by fluxmoe_create.
  */
 int fluxmoe_expert_ffn(fluxmoe_ctx* ctx, uint32_t layer, const uint16_t* tokens, uint32_t T,
                        const int32_t* topk_ids, const float* topk_w, uint32_t K,

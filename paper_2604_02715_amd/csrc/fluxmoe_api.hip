@@ -277,8 +277,9 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     if (d.max_code_len < 8 || d.max_code_len > kLutBits)
         return set_error(FLUXMOE_EINVAL, "max_code_len must be in 8..12 (got %u)", d.max_code_len);
     if (d.flags != 0) return set_error(FLUXMOE_EINVAL, "flags must be 0");
-    if (uint64_t(d.hidden) * d.ffn * 2 >= (1ull << 32))
-        return set_error(FLUXMOE_EINVAL, "a tensor must have fewer than 2^32 elements");
+    if (uint64_t(d.hidden) * d.ffn * 2 >= (1ull << 31))
+        return set_error(FLUXMOE_EINVAL, "hidden * ffn * 2 bytes (one expert matrix) must stay under 2 GiB: "
+                                         "the FFN kernels address a matrix with 32-bit byte offsets");
     if (d.n_experts > 4096) return set_error(FLUXMOE_EINVAL, "n_experts must be <= 4096");
     fluxmoe_ctx* c = new (std::nothrow) fluxmoe_ctx();
     if (!c) return set_error(FLUXMOE_ENOMEM, "out of host memory");
@@ -896,6 +897,8 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, u
     if (K == 0 || K > c->d.n_experts) return set_error(FLUXMOE_EINVAL, "K must be in 1..n_experts");
     if (flags & ~3u) return set_error(FLUXMOE_EINVAL, "unknown flags 0x%x", flags);
     if (uint64_t(T) * K >= (1ull << 31) || T > 65535) return set_error(FLUXMOE_EINVAL, "T too large");
+    if (uint64_t(T) * c->d.hidden * 2 >= (1ull << 32))
+        return set_error(FLUXMOE_EINVAL, "tokens (T * hidden * 2 bytes) must stay under 4 GiB");
     if ((uintptr_t(tokens) | uintptr_t(out)) & 15) return set_error(FLUXMOE_EINVAL, "tokens/out must be 16-byte aligned");
     const FfnPlan p = plan_ffn(c, T, K);
     if (c->pool_ws_bytes + p.bytes > c->ws_bytes)

@@ -112,7 +112,8 @@ def test_length_limit_parameter():
 
 def test_argument_validation_on_the_host():
     for kw, status in ((dict(hidden=100), -1), (dict(block_bytes=8192), -1), (dict(max_code_len=13), -1),
-                       (dict(n_slots=0), -1), (dict(n_experts=5000), -1)):
+                       (dict(n_slots=0), -1), (dict(n_experts=5000), -1),
+                       (dict(hidden=32768, ffn=32768), -1)):        # one expert matrix of 2 GiB
         args = dict(n_layers=1, n_experts=4, hidden=64, ffn=64, n_slots=2)
         args.update(kw)
         with pytest.raises(B.FluxmoeError) as ei:
