@@ -136,9 +136,9 @@ __device__ __forceinline__ uint32_t comp(const uint4& v, int i) {
 }
 
 // k chunks per wavefront held in the register ring (one being multiplied, the rest in flight)
-template <int MI> struct RingDepth { static constexpr int value = MI >= 4 ? 3 : 4; };
+template <int MI> struct RingDepth { static constexpr int value = MI >= 8 ? 2 : (MI >= 4 ? 3 : 4); };
 // the smaller body a kernel for tiles of 16 MI rows also carries (for tiles with few rows)
-template <int MI> struct SmallerBody { static constexpr int value = MI == 6 ? 4 : (MI >= 2 ? MI / 2 : 1); };
+template <int MI> struct SmallerBody { static constexpr int value = MI == 6 ? 4 : (MI >= 2 ? MI / 2 : 1); };   // 8 -> 4
 
 // Shared A blocks: the four wavefronts of a workgroup multiply the same rows of A, so a block of
 // kABlock k values of the tile's rows is loaded once per workgroup into LDS (two buffers) instead of
@@ -463,8 +463,13 @@ __device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileIn
 // MFMA tiles (less work per chunk, same registers reserved).
 template <int MI>
 __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
-    __shared__ float xch[2 * MI * 8 * 4][64];     // [pair][mi, c, r][lane]
-    __shared__ __align__(16) uint16_t abuf[2 * StripGemm<MI>::kABufElems];
+    // the accumulator exchange of the epilogue ([pair][mi, c, r][lane] floats) reuses the memory of
+    // the shared A blocks: every wavefront has passed the last block's barrier by then
+    constexpr size_t kXchBytes = sizeof(float) * 2 * MI * 8 * 4 * 64;
+    constexpr size_t kABytes = sizeof(uint16_t) * 2 * StripGemm<MI>::kABufElems;
+    __shared__ __align__(16) uint8_t smem[kXchBytes > kABytes ? kXchBytes : kABytes];
+    float (*xch)[64] = reinterpret_cast<float (*)[64]>(smem);
+    uint16_t* abuf = reinterpret_cast<uint16_t*>(smem);
     TileInfo t;
     if (!tile_info(a, blockIdx.y, t)) return;     // uniform over the workgroup
     constexpr int kSmall = SmallerBody<MI>::value;
@@ -1375,20 +1380,22 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
         mark(4, 0);
         return hipGetLastError();
     }
-    if (a.m_tile != 16 && a.m_tile != 32 && a.m_tile != 64 && a.m_tile != 96) return hipErrorInvalidValue;
+    if (a.m_tile != 16 && a.m_tile != 32 && a.m_tile != 64 && a.m_tile != 96 && a.m_tile != 128) return hipErrorInvalidValue;
     // the strip kernels address activations and one expert matrix with 32-bit byte offsets
     if (uint64_t(a.T) * a.H * 2 >= (1ull << 32) || uint64_t(a.H) * a.F * 2 >= (1ull << 31)) return hipErrorInvalidValue;
     mark(2, 1);
     if (a.m_tile == 16) hipLaunchKernelGGL(gemm1_swiglu_kernel<1>, g1, dim3(256), 0, stream, a);
     else if (a.m_tile == 32) hipLaunchKernelGGL(gemm1_swiglu_kernel<2>, g1, dim3(256), 0, stream, a);
     else if (a.m_tile == 64) hipLaunchKernelGGL(gemm1_swiglu_kernel<4>, g1, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(gemm1_swiglu_kernel<6>, g1, dim3(256), 0, stream, a);
+    else if (a.m_tile == 96) hipLaunchKernelGGL(gemm1_swiglu_kernel<6>, g1, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(gemm1_swiglu_kernel<8>, g1, dim3(256), 0, stream, a);
     mark(2, 0);
     mark(3, 1);
     if (a.m_tile == 16) hipLaunchKernelGGL(gemm2_kernel<1>, g2, dim3(256), 0, stream, a);
     else if (a.m_tile == 32) hipLaunchKernelGGL(gemm2_kernel<2>, g2, dim3(256), 0, stream, a);
     else if (a.m_tile == 64) hipLaunchKernelGGL(gemm2_kernel<4>, g2, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(gemm2_kernel<6>, g2, dim3(256), 0, stream, a);
+    else if (a.m_tile == 96) hipLaunchKernelGGL(gemm2_kernel<6>, g2, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(gemm2_kernel<8>, g2, dim3(256), 0, stream, a);
     mark(3, 0);
     const dim3 gc((a.H / 4 + 255) / 256, a.T, 1);
     mark(4, 1);

@@ -129,17 +129,21 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
     const uint64_t pairs = uint64_t(T) * K;
     const uint64_t groups = std::max<uint64_t>(1, std::min<uint64_t>(E, pairs));
     const uint64_t avg = (pairs + groups - 1) / groups;
-    // Row tile: every extra tile of an expert streams that expert's weights again, so the tile
-    // is sized for the mean rows per expert plus four standard deviations of a Poisson count
-    // (the kernels run a half-size body for tiles that are at most half full).
-    const double want = double(avg) + 4.0 * std::sqrt(double(avg));
-    p.m_tile = want > 64 ? 96 : (want > 32 ? 64 : (want > 16 ? 32 : 16));
-    // more rows per expert than one 96-row tile: the LDS-tiled MFMA kernels, one pass over the
-    // weights for up to 256 rows (they need k extents that are multiples of 64)
-    if (want > 96 && H % 64 == 0 && F % 64 == 0) p.m_tile = 256;
+    // Row tile of the weight-streaming kernels: every extra tile of an expert streams that expert's
+    // weights again, so the tile is the smallest one that an expert's row count (taken as normal
+    // with mean and variance avg, a Poisson count) exceeds with probability <= 2 %.  When even 128
+    // rows do not meet that, 128-row tiles stay the choice while the expected number of passes per
+    // expert is below 1.6 - what one pass of the LDS-tiled MFMA kernels (256-row tiles, k extents
+    // that are multiples of 64) costs relative to a streaming pass at these sizes.
+    auto p_over = [&](double m) { return 0.5 * std::erfc((m + 0.5 - double(avg)) / std::sqrt(2.0 * double(avg))); };
+    p.m_tile = 128;
+    for (uint32_t m : {16u, 32u, 64u, 96u, 128u})
+        if (p_over(m) <= 0.02) { p.m_tile = m; break; }
+    if (p_over(128) > 0.02 && 1.0 + p_over(128) + p_over(256) + p_over(384) > 1.6 && H % 64 == 0 && F % 64 == 0)
+        p.m_tile = 256;
     if (const char* v = std::getenv("FLUXMOE_FFN_MTILE")) {
         const int m = std::atoi(v);
-        if (m == 16 || m == 32 || m == 64 || m == 96 || (m == 256 && H % 64 == 0 && F % 64 == 0)) p.m_tile = uint32_t(m);
+        if (m == 16 || m == 32 || m == 64 || m == 96 || m == 128 || (m == 256 && H % 64 == 0 && F % 64 == 0)) p.m_tile = uint32_t(m);
     }
     p.pairs_cap = uint32_t(std::max<uint64_t>(pairs, 1));
     p.tiles_cap = uint32_t(pairs / p.m_tile + groups + 1);

@@ -69,6 +69,9 @@ def test_c1_tiny():
     dict(tokens=200, top_k=2, n_experts=3, n_slots=3, hidden=136, ffn=264),   # same rows, shapes the tiled path
                                                                # cannot take: two 96-row tiles per expert
     dict(tokens=256, top_k=2, hidden=320, ffn=448),            # about 64 rows per expert: 96-row tiles, both bodies
+    dict(tokens=170, top_k=2, n_experts=4, n_slots=4),         # about 85 rows per expert: 128-row tiles
+    dict(tokens=170, top_k=2, n_experts=4, n_slots=4, hidden=200, ffn=328),   # the same with ragged strips and k tails
+    dict(tokens=230, top_k=2, n_experts=4, n_slots=4),         # about 115 rows per expert: 128-row tiles, some experts need two
     dict(tokens=120, top_k=2, routing="zipf"),                 # a popular expert overflows its 64-row tile
     dict(tokens=33, top_k=4, hidden=136, ffn=264, n_experts=5, n_slots=5),
     dict(tokens=16, top_k=8, hidden=256, ffn=4096),            # K split of the second product
