@@ -404,11 +404,17 @@ def bench_ffn_rows(cfg, args):
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": cfg.name + "_ffn_rows", "rows_per_expert": M, "experts": E, "hidden": cfg.hidden,
                    "ffn": cfg.ffn, "tokens": T, "top_k": K},
-        "roofline": {"kernel": "gemm1_swiglu", "bound": "mfma",
-                     "achieved": round(4.0 * cfg.hidden * cfg.ffn * T * K / (g1 * 1e-3) / 1e12, 1),
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(4.0 * cfg.hidden * cfg.ffn * T * K / (g1 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": None, "avg_launch_ms": round(g1, 4)},
+        # below the ridge (2.5 PFLOP/s / 8 TB/s = 312 rows per expert) streaming the weights once bounds the
+        # kernel, above it the matrix cores do
+        "roofline": ({"kernel": "gemm1_swiglu", "bound": "mfma",
+                      "achieved": round(4.0 * cfg.hidden * cfg.ffn * T * K / (g1 * 1e-3) / 1e12, 1),
+                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                      "frac": round(4.0 * cfg.hidden * cfg.ffn * T * K / (g1 * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                      "traffic": None, "avg_launch_ms": round(g1, 4)} if M >= 312 else
+                     {"kernel": "gemm1_swiglu", "bound": "hbm",
+                      "achieved": round(E * cfg.sigma1 / (g1 * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                      "frac": round(E * cfg.sigma1 / (g1 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                      "traffic": None, "algorithmic_bytes_per_launch": E * cfg.sigma1, "avg_launch_ms": round(g1, 4)}),
         "ffn": {"frac_mfma_peak": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                 "gemm2_TFLOPs": round(2.0 * cfg.hidden * cfg.ffn * T * K / (g2 * 1e-3) / 1e12, 1),
                 "kernels_ms": {k: round(prof[k][0] / max(1, prof[k][1]), 4)
