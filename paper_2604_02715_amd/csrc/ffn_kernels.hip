@@ -1137,46 +1137,46 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     // LOAD_B: B of step s + 2 (issued in sub-step 0); LOAD_A: A of step s + 2 (after the barrier);
     // NEXT: another step follows.
     int a_own = 0, b_own = 0;                                // byte offsets of this step's stages
-    auto step = [&](uint32_t k0, auto LOAD_B, auto LOAD_A, auto NEXT) __attribute__((always_inline)) {
+    auto step = [&](uint32_t k0, auto LOAD_B, auto LOAD_A, auto NEXT, auto ACT) __attribute__((always_inline)) {
         const int b_plus2 = b_own >= kStageBytes ? b_own - kStageBytes : b_own + 2 * kStageBytes;   // stage of step s + 2
 #pragma unroll
         for (int n = 0; n < 8; ++n) {                         // sub-step 0 (set 0)
-            mfma_item(0, n);
-            lfrag_item(0, 1, 1, n);
+            if (ACT.value) mfma_item(0, n);
+            if (ACT.value) lfrag_item(0, 1, 1, n);
             if (LOAD_B.value && (n & 1)) dma_b(k0 + 2 * kTK, b_plus2, n >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        lfrag_item(0, 1, 1, 8);
-        lfrag_item(0, 1, 1, 9);
+        if (ACT.value) lfrag_item(0, 1, 1, 8);
+        if (ACT.value) lfrag_item(0, 1, 1, 9);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int n = 0; n < 8; ++n) {                         // sub-step 1 (set 1)
-            mfma_item(1, n);
-            lfrag_item(0, 2, 0, n);
+            if (ACT.value) mfma_item(1, n);
+            if (ACT.value) lfrag_item(0, 2, 0, n);
             __builtin_amdgcn_sched_barrier(0);
         }
-        lfrag_item(0, 2, 0, 8);
-        lfrag_item(0, 2, 0, 9);
+        if (ACT.value) lfrag_item(0, 2, 0, 8);
+        if (ACT.value) lfrag_item(0, 2, 0, 9);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int n = 0; n < 8; ++n) {                         // sub-step 2 (set 0)
-            mfma_item(0, n);
-            lfrag_item(0, 3, 1, n);
+            if (ACT.value) mfma_item(0, n);
+            if (ACT.value) lfrag_item(0, 3, 1, n);
             __builtin_amdgcn_sched_barrier(0);
         }
-        lfrag_item(0, 3, 1, 8);
-        lfrag_item(0, 3, 1, 9);
+        if (ACT.value) lfrag_item(0, 3, 1, 8);
+        if (ACT.value) lfrag_item(0, 3, 1, 9);
         if (LOAD_B.value) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");   // all but this step's own B loads have landed
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();                                      // all reads of this step's stages are in registers
 #pragma unroll
         for (int n = 0; n < 8; ++n) {                         // sub-step 3 (set 1)
-            mfma_item(1, n);
-            if (NEXT.value) lfrag_item(1, 0, 0, n);
+            if (ACT.value) mfma_item(1, n);
+            if (NEXT.value && ACT.value) lfrag_item(1, 0, 0, n);
             if (LOAD_A.value && (n & 1)) dma_a(k0 + 2 * kTK, a_own, n >> 1);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (NEXT.value) {
+        if (NEXT.value && ACT.value) {
             lfrag_item(1, 0, 0, 8);
             lfrag_item(1, 0, 0, 9);
         }
@@ -1204,12 +1204,20 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    // A wavefront whose 64 rows all lie past the tile's last row (tail tiles of an expert) takes part
+    // in the loads and barriers only: with at most 128 rows every SIMD runs one multiplying wavefront
+    // instead of two.
+    auto k_loop = [&](auto ACT) __attribute__((always_inline)) {
+        if (ACT.value) {
 #pragma unroll
-    for (int n = 0; n < 10; ++n) lfrag_item(0, 0, 0, n);
-    uint32_t s = 0;
-    for (; s + 2 < n_steps; ++s) step(s * kTK, Yes{}, Yes{}, Yes{});
-    if (s + 1 < n_steps) step(s * kTK, No{}, No{}, Yes{});
-    step(0, No{}, No{}, No{});
+            for (int n = 0; n < 10; ++n) lfrag_item(0, 0, 0, n);
+        }
+        uint32_t s = 0;
+        for (; s + 2 < n_steps; ++s) step(s * kTK, Yes{}, Yes{}, Yes{}, ACT);
+        if (s + 1 < n_steps) step(s * kTK, No{}, No{}, Yes{}, ACT);
+        step(0, No{}, No{}, No{}, ACT);
+    };
+    if (wm * 64 < t.rows) k_loop(Yes{}); else k_loop(No{});
 
     // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4;
     // fragment j of this wavefront holds tile columns 128 wn + 32 j + q (MODE 2) or, in MODE 1,
