@@ -101,6 +101,16 @@ uint64_t fluxmoe_ffn_workspace_bytes(const fluxmoe_ctx* ctx, uint32_t T, uint32_
                                      int shared_expert);
 
 /*
+ * The launch plan fluxmoe_expert_ffn takes for T tokens with K experts each (host only; for tests
+ * and reports): rows per tile of the grouped products (16..128 = weight-streaming kernels, 256 =
+ * LDS-tiled MFMA kernels) and the number of K splits of the second product.  The plan depends on the
+ * shapes, on T * K / n_experts and on the CU count of the device (256 until a bind call has
+ * queried it).
+ */
+int fluxmoe_ffn_plan(const fluxmoe_ctx* ctx, uint32_t T, uint32_t K, uint32_t* rows_per_tile,
+                     uint32_t* k_splits);
+
+/*
  * Offline compression of one layer's routed experts (Sec. 4.2: "Huffman-encodes only the
  * exponent bits offline and leaves the sign and mantissa bits unchanged").  CPU only,
  * deterministic (independent of n_threads).

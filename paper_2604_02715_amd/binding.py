@@ -74,6 +74,7 @@ EXPORTS = {
     "fluxmoe_destroy": (C.c_int, [C.c_void_p]),
     "fluxmoe_query_sizes": (C.c_int, [C.c_void_p, C.POINTER(Sizes)]),
     "fluxmoe_ffn_workspace_bytes": (C.c_uint64, [C.c_void_p, C.c_uint32, C.c_uint32, C.c_int]),
+    "fluxmoe_ffn_plan": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint32, C.POINTER(C.c_uint32), C.POINTER(C.c_uint32)]),
     "fluxmoe_encode_pool": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p,
                                       C.c_size_t, C.POINTER(C.c_size_t), C.c_int]),
     "fluxmoe_layer_info_get": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(LayerInfo)]),
@@ -169,6 +170,13 @@ def fluxmoe_query_sizes(ctx) -> Sizes:
 
 def fluxmoe_ffn_workspace_bytes(ctx, T, K, shared_expert=False) -> int:
     return int(lib().fluxmoe_ffn_workspace_bytes(ctx, T, K, int(shared_expert)))
+
+
+def fluxmoe_ffn_plan(ctx, T, K):
+    """(rows per tile, K splits of the second product) of the launch plan for T tokens, K experts each."""
+    m, k = C.c_uint32(0), C.c_uint32(0)
+    _check(lib().fluxmoe_ffn_plan(ctx, T, K, C.byref(m), C.byref(k)))
+    return int(m.value), int(k.value)
 
 
 def fluxmoe_encode_pool(ctx, layer, w13_ptr, w2_ptr, dst_ptr, dst_cap, n_threads=8) -> int:

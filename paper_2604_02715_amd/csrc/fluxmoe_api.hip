@@ -365,6 +365,15 @@ uint64_t fluxmoe_ffn_workspace_bytes(const fluxmoe_ctx* c, uint32_t T, uint32_t 
     return need;
 }
 
+int fluxmoe_ffn_plan(const fluxmoe_ctx* c, uint32_t T, uint32_t K, uint32_t* rows_per_tile, uint32_t* k_splits) {
+    if (!c || !rows_per_tile || !k_splits) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    if (K == 0 || K > c->d.n_experts) return set_error(FLUXMOE_EINVAL, "K must be in 1..n_experts");
+    const FfnPlan p = plan_ffn(c, T, K);
+    *rows_per_tile = p.m_tile;
+    *k_splits = p.ksplit;
+    return FLUXMOE_OK;
+}
+
 int fluxmoe_encode_pool(fluxmoe_ctx* c, uint32_t layer, const uint16_t* w13, const uint16_t* w2,
                         void* dst, size_t dst_cap, size_t* dst_used, int n_threads) {
     if (int rc = check_layer(c, layer, false)) return rc;
