@@ -992,8 +992,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
 
-template <int MODE>
-__global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
+template <int MODE, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
+    // WAVES = 8: wavefronts 4 (rows) x 2 (columns), 64 x 128 each, two per SIMD.  WAVES = 4: 2 x 2,
+    // 128 x 128 each (256 accumulator registers), one per SIMD: a third less LDS read traffic per MFMA.
+    constexpr int kRowTiles = WAVES == 8 ? 2 : 4;            // 32-row MFMA tiles per wavefront
+    constexpr int kWaveRows = 32 * kRowTiles;
+    constexpr int kDma = 32 / WAVES;                         // 1 KiB loads per wavefront, operand and step
+    constexpr int kMfma = 4 * kRowTiles;                     // MFMAs per sub-step
+    constexpr int kFrag = kRowTiles + 8;                     // fragment reads per sub-step
+    static_assert(WAVES == 8 || WAVES == 4, "wavefront layouts");
     extern __shared__ __align__(16) uint16_t lds[];
     const uint32_t K = MODE == 1 ? a.H : a.F;
     const uint32_t N = MODE == 1 ? a.F : a.H;
@@ -1032,10 +1040,10 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     // ---- global sources of this lane's LDS-direct loads (4 for A, 4 for B per step): 32-bit byte
     // offsets from bases that are uniform over the workgroup
     const uint8_t* const a_base = reinterpret_cast<const uint8_t*>(MODE == 1 ? a.tokens : a.hbuf) + size_t(k_begin) * 2;
-    uint32_t a_off[4];
+    uint32_t a_off[kDma];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int r_lds = 8 * (wave * 4 + i) + (lane >> 3);                 // row of the A tile
+    for (int i = 0; i < kDma; ++i) {
+        const int r_lds = 8 * (wave * kDma + i) + (lane >> 3);                 // row of the A tile
         const int piece = (lane & 7) ^ ((r_lds >> 1) & 7);                  // global 16-byte piece held at position lane & 7
         const int32_t r = min(r_lds, t.rows - 1);
         uint32_t row_elems;
@@ -1046,10 +1054,10 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     const size_t mat = size_t(a.H) * a.F;
     const uint8_t* const b_base = reinterpret_cast<const uint8_t*>(
         MODE == 1 ? a.slots13 + size_t(t.slot) * 2 * mat : a.slots2 + size_t(t.slot) * mat + size_t(k_begin) * N);
-    uint32_t b_off[4];
+    uint32_t b_off[kDma];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int k_lds = 2 * (wave * 4 + i) + (lane >> 5);                 // k row of the B tile
+    for (int i = 0; i < kDma; ++i) {
+        const int k_lds = 2 * (wave * kDma + i) + (lane >> 5);                 // k row of the B tile
         const int pp = lane & 31;                                           // physical 16-byte piece in the row
         const int unit = (pp >> 2) ^ (k_lds & 3);                           // logical unit of 32 columns
         const uint32_t c = 32u * unit + 8u * (pp & 3);                      // column inside the 256-column tile
@@ -1072,17 +1080,17 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     };
     // a_stage_off / b_stage_off: byte offset of the destination stage inside the operand's region, uniform
     auto dma_a = [&](uint32_t k0, int a_stage_off, int n) __attribute__((always_inline)) {
-        dma16(a_base + size_t(k0) * 2 + a_off[n], lds_base + a_stage_off + (wave * 4 + n) * 1024);
+        dma16(a_base + size_t(k0) * 2 + a_off[n], lds_base + a_stage_off + (wave * kDma + n) * 1024);
     };
     auto dma_b = [&](uint32_t k0, int b_stage_off, int n) __attribute__((always_inline)) {
-        dma16(b_base + size_t(k0) * N * 2 + b_off[n], lds_base + 2 * kStageBytes + b_stage_off + (wave * 4 + n) * 1024);
+        dma16(b_base + size_t(k0) * N * 2 + b_off[n], lds_base + 2 * kStageBytes + b_stage_off + (wave * kDma + n) * 1024);
     };
 
     // ---- fragment addresses (bytes from the start of stage 0 of the operand's region)
-    int a_addr[2][4];
+    int a_addr[kRowTiles][4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int R = wm * 64 + 32 * i + q;
+    for (int i = 0; i < kRowTiles; ++i) {
+        const int R = wm * kWaveRows + 32 * i + q;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) a_addr[i][ks] = R * 128 + 16 * ((2 * ks + h) ^ ((R >> 1) & 7));
     }
@@ -1095,26 +1103,26 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
         b_addr[j] = 2 * kStageBytes + (8 * h + e) * 512 + 64 * unit + 32 * nh + 8 * g;
     }
 
-    f32x16 acc[2][4];
+    f32x16 acc[kRowTiles][4];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    bf16x8 fa[2][2];
+    bf16x8 fa[2][kRowTiles];
     i16x4 fb_lo[2][4], fb_hi[2][4];
-    // item n of the 10 fragment reads of sub-step ks from `stage` into register set `set`:
-    // 0..1 A tiles, 2..9 the two halves (k 0..3 and 4..7 of the lane's 8) of the four B fragments
+    // item n of the kFrag fragment reads of sub-step ks from `stage` into register set `set`: first the
+    // A tiles, then the two halves (k 0..3 and 4..7 of the lane's 8) of the four B fragments
     // OTHER: read from the next step's stage instead of the one the address registers point at
     // (A: the other of two stages; B: b_next_delta bytes further in its ring of three)
     int b_next_delta = kStageBytes;
     auto lfrag_item = [&](int other, int ks, int set, int n) __attribute__((always_inline)) {
-        if (n < 2) {
+        if (n < kRowTiles) {
             fa[set][n] = *reinterpret_cast<const bf16x8*>(lds_b8 + (a_addr[n][ks] ^ (other ? kStageBytes : 0)));
         } else {
-            const int j = (n - 2) >> 1, tt = (n - 2) & 1;
+            const int j = (n - kRowTiles) >> 1, tt = (n - kRowTiles) & 1;
             const i16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
                 (lds_i16x4*)(lds_b8 + ((b_addr[j] + (other ? b_next_delta : 0)) + ks * 8192 + tt * 2048)));
             if (tt == 0) fb_lo[set][j] = v; else fb_hi[set][j] = v;
@@ -1139,51 +1147,35 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     int a_own = 0, b_own = 0;                                // byte offsets of this step's stages
     auto step = [&](uint32_t k0, auto LOAD_B, auto LOAD_A, auto NEXT, auto ACT) __attribute__((always_inline)) {
         const int b_plus2 = b_own >= kStageBytes ? b_own - kStageBytes : b_own + 2 * kStageBytes;   // stage of step s + 2
+        // one sub-step: the MFMAs of register set `set`, between them the fragment reads of sub-step
+        // next_ks into the other set (other = 1: from the next step's stages) and this step's share of loads
+        auto sub = [&](int set, int other, int next_ks, auto READ, auto DMA_B, auto DMA_A) __attribute__((always_inline)) {
 #pragma unroll
-        for (int n = 0; n < 8; ++n) {                         // sub-step 0 (set 0)
-            if (ACT.value) mfma_item(0, n);
-            if (ACT.value) lfrag_item(0, 1, 1, n);
-            if (LOAD_B.value && (n & 1)) dma_b(k0 + 2 * kTK, b_plus2, n >> 1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (ACT.value) lfrag_item(0, 1, 1, 8);
-        if (ACT.value) lfrag_item(0, 1, 1, 9);
-        __builtin_amdgcn_sched_barrier(0);
+            for (int n = 0; n < kMfma; ++n) {
+                if (ACT.value) mfma_item(set, n);
+                if (READ.value && ACT.value && n < kFrag) lfrag_item(other, next_ks, set ^ 1, n);
+                if (DMA_B.value && (n & 1)) dma_b(k0 + 2 * kTK, b_plus2, n >> 1);
+                if (DMA_A.value && (n & 1)) dma_a(k0 + 2 * kTK, a_own, n >> 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (READ.value && ACT.value) {
 #pragma unroll
-        for (int n = 0; n < 8; ++n) {                         // sub-step 1 (set 1)
-            if (ACT.value) mfma_item(1, n);
-            if (ACT.value) lfrag_item(0, 2, 0, n);
+                for (int n = kMfma; n < kFrag; ++n) lfrag_item(other, next_ks, set ^ 1, n);
+            }
             __builtin_amdgcn_sched_barrier(0);
-        }
-        if (ACT.value) lfrag_item(0, 2, 0, 8);
-        if (ACT.value) lfrag_item(0, 2, 0, 9);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int n = 0; n < 8; ++n) {                         // sub-step 2 (set 0)
-            if (ACT.value) mfma_item(0, n);
-            if (ACT.value) lfrag_item(0, 3, 1, n);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (ACT.value) lfrag_item(0, 3, 1, 8);
-        if (ACT.value) lfrag_item(0, 3, 1, 9);
-        if (LOAD_B.value) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");   // all but this step's own B loads have landed
+        };
+        using T = std::integral_constant<bool, true>;
+        using F = std::integral_constant<bool, false>;
+        sub(0, 0, 1, T{}, LOAD_B, F{});                       // sub-step 0
+        sub(1, 0, 2, T{}, F{}, F{});                          // sub-step 1
+        sub(0, 0, 3, T{}, F{}, F{});                          // sub-step 2
+        if (LOAD_B.value) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kDma) : "memory");   // all but this step's own B loads have landed
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();                                      // all reads of this step's stages are in registers
-#pragma unroll
-        for (int n = 0; n < 8; ++n) {                         // sub-step 3 (set 1)
-            if (ACT.value) mfma_item(1, n);
-            if (NEXT.value && ACT.value) lfrag_item(1, 0, 0, n);
-            if (LOAD_A.value && (n & 1)) dma_a(k0 + 2 * kTK, a_own, n >> 1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (NEXT.value && ACT.value) {
-            lfrag_item(1, 0, 0, 8);
-            lfrag_item(1, 0, 0, 9);
-        }
-        __builtin_amdgcn_sched_barrier(0);
+        sub(1, 1, 0, NEXT, F{}, LOAD_A);                      // sub-step 3
         // advance to the next step's stages
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) a_addr[i][ks] ^= kStageBytes;
 #pragma unroll
@@ -1197,10 +1189,10 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
 
     // prologue: A of steps 0 and 1, B of steps 0 and 1 (B of step 2 is issued by step 0)
 #pragma unroll
-    for (int n = 0; n < 4; ++n) { dma_a(0, 0, n); dma_b(0, 0, n); }
+    for (int n = 0; n < kDma; ++n) { dma_a(0, 0, n); dma_b(0, 0, n); }
     if (n_steps > 1) {
 #pragma unroll
-        for (int n = 0; n < 4; ++n) { dma_a(kTK, kStageBytes, n); dma_b(kTK, kStageBytes, n); }
+        for (int n = 0; n < kDma; ++n) { dma_a(kTK, kStageBytes, n); dma_b(kTK, kStageBytes, n); }
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
@@ -1210,14 +1202,14 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
     auto k_loop = [&](auto ACT) __attribute__((always_inline)) {
         if (ACT.value) {
 #pragma unroll
-            for (int n = 0; n < 10; ++n) lfrag_item(0, 0, 0, n);
+            for (int n = 0; n < kFrag; ++n) lfrag_item(0, 0, 0, n);
         }
         uint32_t s = 0;
         for (; s + 2 < n_steps; ++s) step(s * kTK, Yes{}, Yes{}, Yes{}, ACT);
         if (s + 1 < n_steps) step(s * kTK, No{}, No{}, Yes{}, ACT);
         step(0, No{}, No{}, No{}, ACT);
     };
-    if (wm * 64 < t.rows) k_loop(Yes{}); else k_loop(No{});
+    if (wm * kWaveRows < t.rows) k_loop(Yes{}); else k_loop(No{});
 
     // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4;
     // fragment j of this wavefront holds tile columns 128 wn + 32 j + q (MODE 2) or, in MODE 1,
@@ -1227,10 +1219,10 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
         // columns (q, q + 1) of an even row and odd lanes columns (q - 1, q) of the next row: 4-byte
         // stores instead of 2-byte ones
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
-                const int32_t row = wm * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3) + (q & 1);
+                const int32_t row = wm * kWaveRows + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3) + (q & 1);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     uint32_t hb[2];
@@ -1250,10 +1242,10 @@ __global__ __launch_bounds__(512) void gemm_d2l_kernel(FfnArgs a) {
             }
     } else {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int32_t row = wm * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+                const int32_t row = wm * kWaveRows + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
                 if (row >= t.rows) continue;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -1342,8 +1334,9 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
     if (a.m_tile == 256) {
         const size_t lds_bytes = 4 * size_t(kTM) * kLdsPitch * sizeof(uint16_t);
         const bool four = a.tiled_waves == 4;
-        const bool d2l = a.tiled_waves == 2;
-        if (!d2l && a.ksplit != 1) return hipErrorInvalidValue;     // only the LDS-direct kernel splits K
+        const bool d2l4 = a.tiled_waves == 1;                       // LDS-direct loads, four wavefronts of 128 x 128
+        const bool d2l = a.tiled_waves == 2 || d2l4;
+        if (!d2l && a.ksplit != 1) return hipErrorInvalidValue;     // only the LDS-direct kernels split K
         if (a.ksplit == 0 || a.ksplit > a.F / kTK) return hipErrorInvalidValue;
         static bool attr_set = false;
         if (!attr_set) {
@@ -1359,10 +1352,16 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled4_kernel<2>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<1>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<1, 8>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<2>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<2, 8>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<1, 4>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
+            if (e != hipSuccess) return e;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<2, 4>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
             if (e != hipSuccess) return e;
             attr_set = true;
@@ -1373,12 +1372,14 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
             const uint32_t supers = (n_sm * n_sn * n_split + 7) / 8 * 8;      // whole rounds over the 8 XCDs
             return dim3(supers * kSuperM * kSuperN, 1, 1);
         };
-        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), 163840, stream, a);
+        if (d2l4) hipLaunchKernelGGL((gemm_d2l_kernel<1, 4>), grid_for((a.F + 127) / 128), dim3(256), 163840, stream, a);
+        else if (d2l) hipLaunchKernelGGL((gemm_d2l_kernel<1, 8>), grid_for((a.F + 127) / 128), dim3(512), 163840, stream, a);
         else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<1>, grid_for((a.F + 127) / 128), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), lds_bytes, stream, a);
         mark(2, 0);
         mark(3, 1);
-        if (d2l) hipLaunchKernelGGL(gemm_d2l_kernel<2>, grid_for((a.H + 255) / 256, a.ksplit), dim3(512), 163840, stream, a);
+        if (d2l4) hipLaunchKernelGGL((gemm_d2l_kernel<2, 4>), grid_for((a.H + 255) / 256, a.ksplit), dim3(256), 163840, stream, a);
+        else if (d2l) hipLaunchKernelGGL((gemm_d2l_kernel<2, 8>), grid_for((a.H + 255) / 256, a.ksplit), dim3(512), 163840, stream, a);
         else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<2>, grid_for((a.H + 255) / 256), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), lds_bytes, stream, a);
         mark(3, 0);

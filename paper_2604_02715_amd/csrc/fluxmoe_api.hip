@@ -168,7 +168,7 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
         // than the chip has CUs, the LDS-direct kernel splits K so that about one workgroup per CU runs
         // (each split keeps at least 8 steps of 64)
         p.ksplit = 1;
-        if (c->tune_tiled_waves == 2) {
+        if (c->tune_tiled_waves == 2 || c->tune_tiled_waves == 1) {
             const uint64_t tiles2 = groups * ((avg + 255) / 256) * ((H + 255) / 256);
             uint64_t k2 = std::max<uint64_t>(1, uint64_t(std::max(c->n_cus, 1)) / tiles2);
             k2 = std::min<uint64_t>(k2, 8);
@@ -311,7 +311,7 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     }
     if (const char* v = std::getenv("FLUXMOE_FFN_TILED_WAVES")) {
         const int w = std::atoi(v);
-        if (w == 2 || w == 4 || w == 8) c->tune_tiled_waves = w;
+        if (w == 1 || w == 2 || w == 4 || w == 8) c->tune_tiled_waves = w;
     }
     *out_ctx = c;
     g_err[0] = 0;

@@ -92,11 +92,12 @@ def test_shapes(kw):
 ])
 def test_variants_of_the_tiled_kernels(monkeypatch, kw):
     """FLUXMOE_FFN_TILED_WAVES selects the variant of the LDS-tiled kernels: 2 (default) loads both
-    operands straight into LDS, 8 and 4 stage them through registers with eight or four wavefronts.
+    operands straight into LDS with eight wavefronts, 1 does the same with four wavefronts of 128 x 128,
+    8 and 4 stage them through registers with eight or four wavefronts.
     All accumulate over k in the same order, so they must agree to rounding."""
     cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], **kw)
     default = run_ffn_case(cfg, seed=1)
-    for variant in ("8", "4", "2"):
+    for variant in ("8", "4", "2", "1"):
         monkeypatch.setenv("FLUXMOE_FFN_TILED_WAVES", variant)
         other = run_ffn_case(cfg, seed=1)
         assert offn.rel_frobenius(other, default) < 1e-5, variant
