@@ -651,9 +651,69 @@ def cpu_baseline(pool, cfg, blob, w13, w2, budget_s):
             n_blocks_done += nb
             tensors += 1
     dt = time.perf_counter() - t0
-    return {"value": round(2.0 * elems / dt / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "oracle/codec.decode_tensor on the first %d tensors of this pool in blob order "
-                      "(%d blocks, %d elements, %.1f s, numpy, one thread)" % (tensors, n_blocks_done, elems, dt)}
+    res = {"value": round(2.0 * elems / dt / 1e9, 5), "unit": "GB/s", "cores": 1, "kind": "oracle",
+           "sample": "oracle/codec.decode_tensor on the first %d tensors of this pool in blob order "
+                     "(%d blocks, %d elements, %.1f s, numpy, one thread)" % (tensors, n_blocks_done, elems, dt)}
+    try:
+        res["all_cores"] = cpu_baseline_all_cores(pool, cfg, blocks, w2, max(1, tensors))
+    except Exception as exc:                                  # the single-thread figure stands on its own
+        res["all_cores"] = {"error": str(exc)[:200]}
+    return res
+
+
+_WORKER = r'''
+import sys, time, numpy as np
+sys.path.insert(0, sys.argv[1])
+from oracle import codec
+d = np.load(sys.argv[2])
+blocks, lens, n_elems, want = d["blocks"], d["lens"], int(d["n_elems"]), d["want"]
+t_start = float(sys.argv[3])
+while time.time() < t_start:
+    time.sleep(0.001)
+t0 = time.perf_counter()
+got = codec.decode_tensor(blocks, lens, n_elems, chunk=256)
+dt = time.perf_counter() - t0
+assert np.array_equal(got, want), "oracle decode mismatch"
+print("%d %.6f %.6f" % (got.size, dt, time.time()))
+'''
+
+
+def cpu_baseline_all_cores(pool, cfg, blocks, w2, per_core_tensors):
+    """The same oracle decode on every host core at once: one child process per core (the oracle is
+    numpy under the interpreter lock, threads do not scale), each decoding one down tensor of the
+    pool (experts round robin); the children import numpy and oracle/ only and start together.
+    Throughput = all decoded bytes / (last finish - common start)."""
+    import subprocess
+    import tempfile
+    import numpy as np
+    from paper_2604_02715_amd import binding as B
+    from paper_2604_02715_amd import inputs
+
+    cores = max(1, min(16, os.cpu_count() or 1))
+    lens = np.asarray(B.fluxmoe_code_lengths(pool.ctx, 0, 2))
+    with tempfile.TemporaryDirectory(dir="/dev/shm" if os.path.isdir("/dev/shm") else None) as tmp:
+        files = []
+        for i in range(cores):
+            e = i % cfg.n_experts
+            b0, nb = B.fluxmoe_tensor_blocks(pool.ctx, 0, 2, e)
+            want = inputs.bits_u16(w2[e]).reshape(-1)
+            f = os.path.join(tmp, "t%d.npz" % i)
+            np.savez(f, blocks=blocks[b0:b0 + nb], lens=lens, n_elems=want.size, want=want)
+            files.append(f)
+        t_start = time.time() + 4.0                           # interpreter and numpy start-up happen before it
+        procs = [subprocess.Popen([sys.executable, "-c", _WORKER, ROOT, f, repr(t_start)],
+                                  stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True) for f in files]
+        elems, t_end = 0, t_start
+        for pr in procs:
+            out, err = pr.communicate(timeout=600)
+            if pr.returncode != 0:
+                raise RuntimeError("oracle worker failed: " + err[-300:])
+            n, _, t_fin = out.split()
+            elems += int(n)
+            t_end = max(t_end, float(t_fin))
+    dt = t_end - t_start
+    return {"value": round(2.0 * elems / dt / 1e9, 5), "unit": "GB/s", "cores": cores,
+            "sample": "one down tensor per core, %d processes started together (%d elements, %.1f s)" % (cores, elems, dt)}
 
 
 if __name__ == "__main__":
