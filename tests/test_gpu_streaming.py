@@ -73,9 +73,27 @@ def test_staging_too_small_is_an_error():
         pool.close()
 
 
-def test_overlapped_schedule_matches_oracle_and_single_stream_schedule():
-    cfg = small_stream_cfg()
-    pool, dense, stats = build(cfg)
+def build_whole_tensor_tiers(cfg):
+    """Every layer keeps three down tensors and one fused tensor dense in pinned host memory (tier 2),
+    two more down tensors compressed in pinned host memory (tier 1), the rest compressed on the device."""
+    pool = harness.ExpertPool(cfg)
+    dense = {}
+    E = cfg.n_experts
+    for layer in range(cfg.n_layers):
+        w13, w2 = harness.make_layer_on_host(cfg, layer)
+        blob = pool.encode_layer(layer, w13, w2)
+        pool.bind_layer(layer, blob, 0.0)
+        pool.place_tensors_raw_on_host(layer, [((2, e), w2[e]) for e in (E - 1, E - 2, E - 3)] + [((1, E - 1), w13[E - 1])])
+        pool.place_tensors_on_host(layer, blob, [(2, 0), (2, 1)])
+        dense[layer] = (w13, w2)
+    pool.bind_staging(2 * (3 * cfg.sigma2 + cfg.sigma1 + 2 * cfg.sigma2) + 16384)
+    return pool, dense, None
+
+
+@pytest.mark.parametrize("tiers", ["block_prefix", "whole_tensors_dense_and_compressed"])
+def test_overlapped_schedule_matches_oracle_and_single_stream_schedule(tiers):
+    cfg = small_stream_cfg(host_fraction=0.40 if tiers == "block_prefix" else 0.0)
+    pool, dense, stats = build(cfg) if tiers == "block_prefix" else build_whole_tensor_tiers(cfg)
     try:
         routings = [inputs.routing(cfg, layer) for layer in range(cfg.n_layers)]
         xs_host = [inputs.activations(cfg, layer) for layer in range(cfg.n_layers)]
