@@ -16,8 +16,12 @@
 // MFMA wants 8 consecutive k per lane.  Each lane therefore loads 8 rows x 16 bytes (8
 // columns) straight from HBM, fully coalesced along N, and transposes its 8x8 tile in
 // registers with v_perm_b32; MFMA number c of a step uses column c of every lane's tile,
-// so output column j of that MFMA is column 8 * j + c of the strip.  No LDS is involved
-// and every weight byte is read exactly once per row tile.
+// so output column j of that MFMA is column 8 * j + c of the strip.  Weights never pass
+// through LDS and every weight byte is read exactly once per row tile; LDS holds only the
+// tile's activations, shared by the four wavefronts of a workgroup.
+// Batches with more rows per expert than one 128-row tile go to the LDS-tiled kernels
+// further down (gemm_d2l_kernel and its register-staged predecessors), which are bound by
+// the matrix cores.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
