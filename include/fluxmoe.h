@@ -101,18 +101,8 @@ uint64_t fluxmoe_ffn_workspace_bytes(const fluxmoe_ctx* ctx, uint32_t T, uint32_
                                      int shared_expert);
 
 /*
- * The launch plan fluxmoe_expert_ffn takes for T tokens with K experts each (host only; for tests
- * and reports): rows per tile of the grouped products (16..128 = weight-streaming kernels, 256 =
- * LDS-tiled MFMA kernels) and the number of K splits of the second product.  The plan depends on the
- * shapes, on T * K / n_experts and on the CU count of the device (256 until a bind call has
- * queried it).
- */
-int fluxmoe_ffn_plan(const fluxmoe_ctx* ctx, uint32_t T, uint32_t K, uint32_t* rows_per_tile,
-                     uint32_t* k_splits);
-
-/*
- * Offline compression of one layer's routed experts (Sec. 4.2: "Huffman-encodes only the
- * exponent bits offline and leaves the sign and mantissa bits unchanged").  CPU only,
+ * Offline compression of one layer's routed experts (Sec. 4.2 "Compressed GPU backend": only the
+ * exponent field is entropy coded, ahead of serving; sign and mantissa are stored as they are).  CPU only,
  * deterministic (independent of n_threads).
  *   w13  host, BF16 bit patterns [n_experts][2][hidden][ffn]  (gate, then up; y = x W)
  *   w2   host, BF16 bit patterns [n_experts][ffn][hidden]
@@ -197,7 +187,8 @@ int fluxmoe_reset_page_table(fluxmoe_ctx* ctx, int32_t* page_table, void* stream
  * Host-tier fetch (Sec. 4.2 "CPU offload backend": asynchronous DMA from pinned host
  * memory, overlapped with inference).  Enqueues on copy_stream the hipMemcpyAsync of every
  * host-tier block the listed experts of `layer` need into the staging half of that layer,
- * after waiting (on the device) for the last decode that read that half.  Layer l uses half
+ * after waiting (on the device) for the last decode that read that half and for the copies
+ * of the previous fetch into it (which may have been issued on another stream).  Layer l uses half
  * l & 1 and the half keeps the blocks until the next fetch into it, so one fetch can serve
  * several fluxmoe_materialize calls (waves) of that layer over subsets of the listed experts;
  * each of them waits for these copies.  Issue the fetch for layer l + 2 only after the last
@@ -208,8 +199,8 @@ int fluxmoe_prefetch_host(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* exper
                           uint32_t n, void* copy_stream);
 
 /*
- * Materialize experts of one layer into staging slots (Sec. 3: "materialized only when
- * their layer is scheduled"; Alg. 1 MaterializeLayer).
+ * Materialize experts of one layer into staging slots (Sec. 3 "Expert paging": a layer's experts
+ * become resident only for the time the layer is scheduled; Alg. 1 MaterializeLayer).
  *   expert_ids host, n distinct ids in [0, n_experts)
  *   dst_slots  host, n distinct slots in [0, n_slots)
  *   page_table device int32 [n_layers][n_experts]; the same table on every call
@@ -225,11 +216,16 @@ int fluxmoe_materialize(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_
                         void* stream);
 
 /*
- * Release experts of one layer (Sec. 3: "After the MoE block of layer i-1 completes, the
- * proxy releases E_{i-1}"): enqueue page_table[layer][e] = -1 for the listed experts that are
- * mapped; their slots become free for reuse (a later materialize into them still waits for
- * the FFN that last read them).  expert_ids NULL with n = 0 releases every expert of the
- * layer.  Slot contents are not touched.
+ * Release experts of one layer (Sec. 3 "Expert paging": once a layer's MoE block has run, the
+ * forward proxy gives that layer's expert set back): enqueue page_table[layer][e] = -1 for the
+ * listed experts that are mapped; their slots become free for reuse (a later materialize into
+ * them still waits for the FFN that last read them).  expert_ids NULL with n = 0 releases every
+ * expert of the layer.  Slot contents are not touched.
+ * Stream contract: the update is enqueued on `stream` after waiting (on the device) for the
+ * layer's last fluxmoe_expert_ffn and last fluxmoe_materialize, whatever streams those ran on;
+ * a later fluxmoe_materialize or fluxmoe_expert_ffn of the same layer waits for the release.
+ * Calls of one kind for one layer (two materializes, two releases) must be ordered by the
+ * caller: same stream, or the caller's own events.
  */
 int fluxmoe_release(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_ids, uint32_t n,
                     int32_t* page_table, void* stream);
@@ -257,41 +253,6 @@ int fluxmoe_release(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_ids,
 int fluxmoe_expert_ffn(fluxmoe_ctx* ctx, uint32_t layer, const uint16_t* tokens, uint32_t T,
                        const int32_t* topk_ids, const float* topk_w, uint32_t K,
                        const int32_t* page_table, float* out, uint32_t flags, void* stream);
-
-/*
- * Measurement aid: a plain device-to-device copy of `bytes` bytes (multiple of 16, both
- * pointers 16-byte aligned) with the same streaming 16-byte accesses the decode kernel
- * uses, on n_workgroups workgroups of 256 lanes.  Gives the achievable HBM rate on the box
- * and a known-traffic kernel for calibrating hardware counters.  Needs no context.
- */
-int fluxmoe_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_workgroups,
-                        void* stream);
-
-/*
- * Measurement aid: n_workgroups workgroups of four wavefronts each issue iters x 16 independent
- * v_mfma_f32_32x32x16_bf16 (32768 flops each) on operands taken once from `operands` (device, 64 KiB
- * of BF16 values, 16-byte aligned) and no memory traffic in the loop; `out` (device, n_workgroups *
- * 256 floats) receives sums that keep the work alive.  Timed by the caller, it gives the rate the
- * matrix cores sustain for that operand content (the chip's clock depends on it).  Needs no context.
- */
-int fluxmoe_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, uint32_t iters,
-                       void* stream);
-
-/*
- * Kernel timing for benchmarks.  While enabled, every kernel the library launches is
- * bracketed by HIP events on its own stream.  fluxmoe_profile_collect waits for them, adds
- * the elapsed milliseconds and launch counts per kind and forgets them:
- *   kind 0 decode + paged scatter, 1 token grouping, 2 gate/up product + SwiGLU,
- *   3 down product, 4 gated combine.
- * on: 0 = off, 1 = every kind, FLUXMOE_PROFILE_ONLY(mask) = only the kinds whose bit is set in
- * mask (an event between two kernels costs a few microseconds of idle device time; a benchmark
- * that times whole steps brackets only the kernel it reports).
- */
-#define FLUXMOE_PROFILE_KINDS 5
-#define FLUXMOE_PROFILE_ONLY(mask) (0x100 | ((mask) & 0x1F))
-int fluxmoe_profile_enable(fluxmoe_ctx* ctx, int on);
-int fluxmoe_profile_collect(fluxmoe_ctx* ctx, double out_ms[FLUXMOE_PROFILE_KINDS],
-                            uint32_t out_count[FLUXMOE_PROFILE_KINDS]);
 
 /*
  * The shared expert of a layer (Sec. 3 excludes shared experts from the routed set; Sec. 4.2
@@ -416,7 +377,8 @@ int fluxmoe_paged_tensor_destroy(fluxmoe_paged_tensor* p);
 int fluxmoe_paged_tensor_info_get(const fluxmoe_paged_tensor* p, fluxmoe_paged_tensor_info* out);
 int fluxmoe_paged_tensor_address(const fluxmoe_paged_tensor* p, uint32_t layer, int type,
                                  uint32_t expert, void** out);
-/* Residency change of one layer (Sec. 4.1: "Only residency changes alter mappings"): remap its
+/* Residency change of one layer (Sec. 4.1: mappings change only when a layer changes residency
+ * class, never on materialization): remap its
  * ranges to a new dedicated block (contents undefined) or back to its reusable block (the
  * dedicated block is released).  Synchronises the device first; addresses do not change. */
 int fluxmoe_paged_tensor_set_class(fluxmoe_paged_tensor* p, uint32_t layer, int uncompressed);
@@ -437,6 +399,56 @@ int fluxmoe_balanced_split(double beta_gpu, double beta_cpu, uint32_t experts_pe
 /* Synchronous: read and clear the device error word (0 = none; bit 0 a block failed
  * validation during decode and was skipped, bit 1 an unmapped expert was routed to). */
 int fluxmoe_device_errors(fluxmoe_ctx* ctx, uint32_t* out_flags);
+
+/* ------------------------------------------------------------------------------------------
+ * Measurement section.  Nothing below is part of the hot path or needed to use it: these entry
+ * points exist for benchmarks, counter calibration and tests of the launch plan.
+ * ------------------------------------------------------------------------------------------ */
+
+/*
+ * The launch plan fluxmoe_expert_ffn takes for T tokens with K experts each (host only; for tests
+ * and reports): rows per tile of the grouped products (16..128 = weight-streaming kernels, 256 =
+ * LDS-tiled MFMA kernels) and the number of K splits of the second product.  The plan depends on the
+ * shapes, on T * K / n_experts and on the CU count of the device (256 until a bind call has
+ * queried it).
+ */
+int fluxmoe_ffn_plan(const fluxmoe_ctx* ctx, uint32_t T, uint32_t K, uint32_t* rows_per_tile,
+                     uint32_t* k_splits);
+
+/*
+ * Measurement aid: a plain device-to-device copy of `bytes` bytes (multiple of 16, both
+ * pointers 16-byte aligned) with the same streaming 16-byte accesses the decode kernel
+ * uses, on n_workgroups workgroups of 256 lanes.  Gives the achievable HBM rate on the box
+ * and a known-traffic kernel for calibrating hardware counters.  Needs no context.
+ */
+int fluxmoe_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_workgroups,
+                        void* stream);
+
+/*
+ * Measurement aid: n_workgroups workgroups of four wavefronts each issue iters x 16 independent
+ * v_mfma_f32_32x32x16_bf16 (32768 flops each) on operands taken once from `operands` (device, 64 KiB
+ * of BF16 values, 16-byte aligned) and no memory traffic in the loop; `out` (device, n_workgroups *
+ * 256 floats) receives sums that keep the work alive.  Timed by the caller, it gives the rate the
+ * matrix cores sustain for that operand content (the chip's clock depends on it).  Needs no context.
+ */
+int fluxmoe_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, uint32_t iters,
+                       void* stream);
+
+/*
+ * Kernel timing for benchmarks.  While enabled, every kernel the library launches is
+ * bracketed by HIP events on its own stream.  fluxmoe_profile_collect waits for them, adds
+ * the elapsed milliseconds and launch counts per kind and forgets them:
+ *   kind 0 decode + paged scatter, 1 token grouping, 2 gate/up product + SwiGLU,
+ *   3 down product, 4 gated combine.
+ * on: 0 = off, 1 = every kind, FLUXMOE_PROFILE_ONLY(mask) = only the kinds whose bit is set in
+ * mask (an event between two kernels costs a few microseconds of idle device time; a benchmark
+ * that times whole steps brackets only the kernel it reports).
+ */
+#define FLUXMOE_PROFILE_KINDS 5
+#define FLUXMOE_PROFILE_ONLY(mask) (0x100 | ((mask) & 0x1F))
+int fluxmoe_profile_enable(fluxmoe_ctx* ctx, int on);
+int fluxmoe_profile_collect(fluxmoe_ctx* ctx, double out_ms[FLUXMOE_PROFILE_KINDS],
+                            uint32_t out_count[FLUXMOE_PROFILE_KINDS]);
 
 #ifdef __cplusplus
 }

@@ -14,10 +14,11 @@
 // contiguous, 128-byte aligned slot memory.  Output positions are static; only bit
 // positions are data dependent.
 //
-// Per pair of symbols a lane re-reads a 32-bit window of its sub-stream from LDS (two
-// words funnel-shifted by the bit position), looks each symbol up in the table (12 peeked
-// bits -> exponent field + length) and advances the position by the two lengths.  Table
-// entries are (exponent << 23) | length: shifting by an entry uses only its low 5 bits,
+// Each lane keeps the unread bits of its sub-stream in a 64-bit reservoir that is topped up
+// from the staged block one 32-bit word at a time, only by the lanes that have run low, so
+// every stream word is fetched from LDS once.  Per symbol the lane looks the reservoir's low
+// 12 bits up in the table (-> exponent field + length) and shifts the reservoir by the length.
+// Table entries are (exponent << 23) | length: shifting by an entry uses only its low bits,
 // adding entries accumulates lengths in the low bits, and the high half of an entry is the
 // exponent already in BF16 position.
 #include <hip/hip_runtime.h>

@@ -84,8 +84,8 @@ struct fluxmoe_ctx {
     std::vector<int32_t> pt;
     std::vector<int64_t> slot_owner;      // layer * E + expert, or -1
     // Alg. 1 state
-    std::vector<hipEvent_t> ev_load, ev_infer;
-    std::vector<uint8_t> load_valid, infer_valid;
+    std::vector<hipEvent_t> ev_load, ev_infer, ev_rel;   // per layer: last materialize / FFN / release
+    std::vector<uint8_t> load_valid, infer_valid, rel_valid;
     std::vector<int32_t> slot_last_reader; // layer whose FFN last read the slot, or -1
     bool events_ready = false;
     // host-tier staging
@@ -95,6 +95,7 @@ struct fluxmoe_ctx {
     hipEvent_t ev_copied[2] = {};           // copies into the half have completed
     hipEvent_t ev_half_done[2] = {};        // last decode that read the half
     bool half_done_valid[2] = {false, false};
+    bool copied_valid[2] = {false, false};  // ev_copied[h] has been recorded
     // launch shape of the decode kernel (FLUXMOE_DECODE_WAVES / FLUXMOE_DECODE_WG_PER_CU override)
     int tune_waves = 8;
     int tune_wg_per_cu = 64;
@@ -123,9 +124,20 @@ void compute_layout(fluxmoe_ctx* c) {
     c->pool_ws_bytes = align_up(c->err_off + 256, 4096);
 }
 
-FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
+// Shapes and launch parameters the FFN plan depends on (a routed layer, or one always-mapped expert
+// for the shared-expert call).
+struct FfnShape {
+    uint64_t E, H, F;
+    int n_cus, tiled_waves;
+};
+
+FfnShape ffn_shape(const fluxmoe_ctx* c, uint32_t n_experts) {
+    return FfnShape{n_experts, c->d.hidden, c->d.ffn, c->n_cus, c->tune_tiled_waves};
+}
+
+FfnPlan plan_ffn(const FfnShape& c, uint32_t T, uint32_t K) {
     FfnPlan p{};
-    const uint64_t E = c->d.n_experts, H = c->d.hidden, F = c->d.ffn;
+    const uint64_t E = c.E, H = c.H, F = c.F;
     const uint64_t pairs = uint64_t(T) * K;
     const uint64_t groups = std::max<uint64_t>(1, std::min<uint64_t>(E, pairs));
     const uint64_t avg = (pairs + groups - 1) / groups;
@@ -153,7 +165,7 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
     // start-up cost) + the FP32 partials it writes and combine_kernel reads back.
     const uint64_t strips2 = (H + 127) / 128;
     const uint64_t est_tiles = std::max<uint64_t>(1, std::max<uint64_t>(pairs / p.m_tile, std::min(groups, pairs)));
-    const uint64_t n_cus = uint64_t(std::max(c->n_cus, 1));
+    const uint64_t n_cus = uint64_t(std::max(c.n_cus, 1));
     uint64_t ks = 1, best_cost = ~0ull;
     for (uint64_t k = 1; k <= 8 && k <= std::max<uint64_t>(1, F / 256); ++k) {
         const uint64_t wgs = (strips2 + 3) / 4 * est_tiles * k;
@@ -168,9 +180,9 @@ FfnPlan plan_ffn(const fluxmoe_ctx* c, uint32_t T, uint32_t K) {
         // than the chip has CUs, the LDS-direct kernel splits K so that about one workgroup per CU runs
         // (each split keeps at least 8 steps of 64)
         p.ksplit = 1;
-        if (c->tune_tiled_waves == 2 || c->tune_tiled_waves == 1) {
+        if (c.tiled_waves == 2 || c.tiled_waves == 1) {
             const uint64_t tiles2 = groups * ((avg + 255) / 256) * ((H + 255) / 256);
-            uint64_t k2 = std::max<uint64_t>(1, uint64_t(std::max(c->n_cus, 1)) / tiles2);
+            uint64_t k2 = std::max<uint64_t>(1, n_cus / tiles2);
             k2 = std::min<uint64_t>(k2, 8);
             k2 = std::min<uint64_t>(k2, std::max<uint64_t>(1, F / 512));
             p.ksplit = uint32_t(k2);
@@ -223,9 +235,11 @@ int ensure_events(fluxmoe_ctx* c) {
     const uint32_t N = c->d.n_layers;
     c->ev_load.assign(N, nullptr);
     c->ev_infer.assign(N, nullptr);
+    c->ev_rel.assign(N, nullptr);
     for (uint32_t i = 0; i < N; ++i) {
         HIPCHECK(hipEventCreateWithFlags(&c->ev_load[i], hipEventDisableTiming));
         HIPCHECK(hipEventCreateWithFlags(&c->ev_infer[i], hipEventDisableTiming));
+        HIPCHECK(hipEventCreateWithFlags(&c->ev_rel[i], hipEventDisableTiming));
     }
     for (int i = 0; i < kRing; ++i)
         HIPCHECK(hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming));
@@ -296,6 +310,7 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     c->slot_last_reader.assign(d.n_slots, -1);
     c->load_valid.assign(d.n_layers, 0);
     c->infer_valid.assign(d.n_layers, 0);
+    c->rel_valid.assign(d.n_layers, 0);
     compute_layout(c);
     if (const char* v = std::getenv("FLUXMOE_DECODE_WAVES")) {
         const int w = std::atoi(v);
@@ -323,6 +338,7 @@ int fluxmoe_destroy(fluxmoe_ctx* c) {
     if (c->events_ready) {
         for (auto e : c->ev_load) if (e) (void)hipEventDestroy(e);
         for (auto e : c->ev_infer) if (e) (void)hipEventDestroy(e);
+        for (auto e : c->ev_rel) if (e) (void)hipEventDestroy(e);
         for (int i = 0; i < kRing; ++i) if (c->ring_ev[i]) (void)hipEventDestroy(c->ring_ev[i]);
         for (int i = 0; i < 2; ++i) if (c->ev_half_done[i]) (void)hipEventDestroy(c->ev_half_done[i]);
         for (int i = 0; i < 2; ++i) if (c->ev_copied[i]) (void)hipEventDestroy(c->ev_copied[i]);
@@ -356,19 +372,16 @@ static uint64_t shared_extra_bytes(uint32_t T) { return 2 * align_up(uint64_t(T)
 
 uint64_t fluxmoe_ffn_workspace_bytes(const fluxmoe_ctx* c, uint32_t T, uint32_t K, int shared_expert) {
     if (!c) return 0;
-    uint64_t need = plan_ffn(c, T, K).bytes;
-    if (shared_expert) {
-        fluxmoe_ctx one = *c;          // same shapes, a single expert
-        one.d.n_experts = 1;
-        need = std::max(need, plan_ffn(&one, T, 1).bytes + shared_extra_bytes(T));
-    }
+    uint64_t need = plan_ffn(ffn_shape(c, c->d.n_experts), T, K).bytes;
+    if (shared_expert)          // same shapes, a single expert
+        need = std::max(need, plan_ffn(ffn_shape(c, 1), T, 1).bytes + shared_extra_bytes(T));
     return need;
 }
 
 int fluxmoe_ffn_plan(const fluxmoe_ctx* c, uint32_t T, uint32_t K, uint32_t* rows_per_tile, uint32_t* k_splits) {
     if (!c || !rows_per_tile || !k_splits) return set_error(FLUXMOE_EINVAL, "NULL argument");
     if (K == 0 || K > c->d.n_experts) return set_error(FLUXMOE_EINVAL, "K must be in 1..n_experts");
-    const FfnPlan p = plan_ffn(c, T, K);
+    const FfnPlan p = plan_ffn(ffn_shape(c, c->d.n_experts), T, K);
     *rows_per_tile = p.m_tile;
     *k_splits = p.ksplit;
     return FLUXMOE_OK;
@@ -685,9 +698,14 @@ static int stage_host_blocks(fluxmoe_ctx* c, uint32_t layer, const int32_t* ids,
         return set_error(FLUXMOE_ENOMEM, "staging half holds %llu bytes, layer %u needs %llu",
                          (unsigned long long)half_bytes, layer, (unsigned long long)cursor);
     if (c->half_done_valid[h]) HIPCHECK(hipStreamWaitEvent(s, c->ev_half_done[h], 0));
+    // an earlier staging into this half may have been issued on another stream (a prefetch on the copy
+    // stream, then a materialize of other experts that restages on its own stream): its copies must
+    // have landed before these overwrite the half with a different layout
+    if (c->copied_valid[h]) HIPCHECK(hipStreamWaitEvent(s, c->ev_copied[h], 0));
     for (const Range& r : ranges)
         HIPCHECK(hipMemcpyAsync(base + r.dst, r.src, r.bytes, hipMemcpyHostToDevice, s));
     HIPCHECK(hipEventRecord(c->ev_copied[h], s));
+    c->copied_valid[h] = true;
     st.layer = layer;
     return FLUXMOE_OK;
 }
@@ -818,6 +836,8 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
 
     // enqueue: WAR waits, host-tier copies, command upload, decode, events
     for (int32_t lr : wait_layers) HIPCHECK(hipStreamWaitEvent(stream, c->ev_infer[lr], 0));
+    // a release of this layer issued on another stream writes the same page-table row
+    if (c->rel_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_rel[layer], 0));
     if (wait_copy) HIPCHECK(hipStreamWaitEvent(stream, c->ev_copied[half], 0));
     const size_t used = upd_off + touched.size() * 8;
     HIPCHECK(hipMemcpyAsync(dcmd, hcmd, used, hipMemcpyHostToDevice, stream));
@@ -892,20 +912,25 @@ int fluxmoe_release(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, u
         ++m;
     }
     if (m == 0) return FLUXMOE_OK;
+    // the entries are read by the layer's FFN and written by its materialize, possibly on other streams
+    if (c->infer_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_infer[layer], 0));
+    if (c->load_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_load[layer], 0));
     HIPCHECK(hipMemcpyAsync(dcmd, hcmd, size_t(m) * 8, hipMemcpyHostToDevice, stream));
     HIPCHECK(launch_apply_updates(page_table, dcmd, m, stream));
+    HIPCHECK(hipEventRecord(c->ev_rel[layer], stream));
+    c->rel_valid[layer] = 1;
     HIPCHECK(hipEventRecord(c->ring_ev[slot], stream));
     c->ring_used[slot] = true;
     c->ring_next = (slot + 1) % kRing;
     return FLUXMOE_OK;
 }
 
-int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, uint32_t T,
-                       const int32_t* topk_ids, const float* topk_w, uint32_t K,
-                       const int32_t* page_table, float* out, uint32_t flags, void* stream_v) {
-    if (int rc = check_layer(c, layer, false)) return rc;
-    if (!c->arenas_bound) return set_error(FLUXMOE_ESTATE, "fluxmoe_bind_arenas has not been called");
-    if (T == 0) return FLUXMOE_OK;
+// Body of fluxmoe_expert_ffn: `w` is the FFN scratch (pair order, tile
+// list, h, split-K partials) of `w_bytes` bytes, `w_name` says where it comes from in error texts.
+static int expert_ffn_enqueue(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, uint32_t T,
+                              const int32_t* topk_ids, const float* topk_w, uint32_t K,
+                              const int32_t* page_table, float* out, uint32_t flags, void* stream_v,
+                              uint8_t* w, uint64_t w_bytes, const char* w_name) {
     if (!tokens || !topk_ids || !topk_w || !page_table || !out) return set_error(FLUXMOE_EINVAL, "NULL argument");
     if (K == 0 || K > c->d.n_experts) return set_error(FLUXMOE_EINVAL, "K must be in 1..n_experts");
     if (flags & ~3u) return set_error(FLUXMOE_EINVAL, "unknown flags 0x%x", flags);
@@ -913,13 +938,12 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, u
     if (uint64_t(T) * c->d.hidden * 2 >= (1ull << 32))
         return set_error(FLUXMOE_EINVAL, "tokens (T * hidden * 2 bytes) must stay under 4 GiB");
     if ((uintptr_t(tokens) | uintptr_t(out)) & 15) return set_error(FLUXMOE_EINVAL, "tokens/out must be 16-byte aligned");
-    const FfnPlan p = plan_ffn(c, T, K);
-    if (c->pool_ws_bytes + p.bytes > c->ws_bytes)
-        return set_error(FLUXMOE_ENOMEM, "workspace has %zu bytes, T=%u K=%u needs %llu", c->ws_bytes, T, K,
-                         (unsigned long long)(c->pool_ws_bytes + p.bytes));
+    const FfnPlan p = plan_ffn(ffn_shape(c, c->d.n_experts), T, K);
+    if (p.bytes > w_bytes)
+        return set_error(FLUXMOE_ENOMEM, "%s holds %llu bytes, T=%u K=%u needs %llu", w_name,
+                         (unsigned long long)w_bytes, T, K, (unsigned long long)p.bytes);
     if (p.tiles_cap > 65535) return set_error(FLUXMOE_EINVAL, "too many row tiles (%u)", p.tiles_cap);
     hipStream_t stream = static_cast<hipStream_t>(stream_v);
-    uint8_t* w = c->ws + c->pool_ws_bytes;
     FfnArgs a{};
     a.tokens = tokens;
     a.topk_ids = topk_ids;
@@ -944,6 +968,7 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, u
     a.tiled_waves = c->tune_tiled_waves;
 
     if (c->load_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_load[layer], 0));
+    if (c->rel_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_rel[layer], 0));
     HIPCHECK(launch_ffn(a, c->n_cus, stream, c->profiling ? ffn_span_hook : nullptr, c));
     HIPCHECK(hipEventRecord(c->ev_infer[layer], stream));
     c->infer_valid[layer] = 1;
@@ -951,6 +976,16 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, u
     for (uint32_t s = 0; s < c->d.n_slots; ++s)
         if (c->slot_owner[s] >= lo && c->slot_owner[s] < hi) c->slot_last_reader[s] = int32_t(layer);
     return FLUXMOE_OK;
+}
+
+int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, uint32_t T,
+                       const int32_t* topk_ids, const float* topk_w, uint32_t K,
+                       const int32_t* page_table, float* out, uint32_t flags, void* stream_v) {
+    if (int rc = check_layer(c, layer, false)) return rc;
+    if (!c->arenas_bound) return set_error(FLUXMOE_ESTATE, "fluxmoe_bind_arenas has not been called");
+    if (T == 0) return FLUXMOE_OK;
+    return expert_ffn_enqueue(c, layer, tokens, T, topk_ids, topk_w, K, page_table, out, flags, stream_v,
+                              c->ws + c->pool_ws_bytes, c->ws_bytes - c->pool_ws_bytes, "the bound workspace past the pool part");
 }
 
 int fluxmoe_shared_expert_ffn(fluxmoe_ctx* c, const uint16_t* w13, const uint16_t* w2,
@@ -964,9 +999,7 @@ int fluxmoe_shared_expert_ffn(fluxmoe_ctx* c, const uint16_t* w13, const uint16_
     if (T > 65535) return set_error(FLUXMOE_EINVAL, "T too large");
     if ((uintptr_t(w13) | uintptr_t(w2) | uintptr_t(tokens) | uintptr_t(out)) & 15)
         return set_error(FLUXMOE_EINVAL, "pointers must be 16-byte aligned");
-    fluxmoe_ctx one = *c;              // shapes of this model with a single, always-mapped expert
-    one.d.n_experts = 1;
-    const FfnPlan p = plan_ffn(&one, T, 1);
+    const FfnPlan p = plan_ffn(ffn_shape(c, 1), T, 1);   // this model's shapes, a single always-mapped expert
     const uint64_t extra = shared_extra_bytes(T);
     if (c->pool_ws_bytes + p.bytes + extra > c->ws_bytes)
         return set_error(FLUXMOE_ENOMEM, "workspace has %zu bytes, the shared expert with T=%u needs %llu",
