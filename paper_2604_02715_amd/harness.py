@@ -230,9 +230,11 @@ class StreamingProxy:
         self.load_stream, self.infer_stream, self.copy_stream = streams or (
             torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
 
-    def run_pass(self, layer_done_events=None, single_stream=False, ffn_delay_cycles=0):
+    def run_pass(self, layer_done_events=None, single_stream=False, ffn_delay_cycles=0, after_wave=None):
         """Issue one pass over all layers.  single_stream=True puts everything on the
         inference stream in program order (the reference schedule for hazard checks).
+        after_wave(layer, wave index, expert ids, slots), if given, is called after a wave's FFN has
+        been issued and before its release (a test synchronises there and inspects the slots).
         ffn_delay_cycles > 0 holds the inference stream back before every FFN (a bounded
         spin kernel), which widens the window in which a missing write-after-read wait would
         let the next materialize overwrite slots that the FFN has not read yet."""
@@ -256,6 +258,8 @@ class StreamingProxy:
                         torch.cuda._sleep(int(ffn_delay_cycles))
                 p.expert_ffn(layer, self.xs[layer], self.ids[layer], self.gates[layer], self.outs[layer],
                              flags, self.infer_stream)
+                if after_wave is not None:
+                    after_wave(layer, wi, w, slots)
                 p.release(layer, w, self.infer_stream)
             if layer_done_events is not None:
                 layer_done_events[layer].record(self.infer_stream)

@@ -4,7 +4,9 @@ Decoded weights: every byte of every materialized slot is compared (on the devic
 original dense tensor, which is the definition of the lossless result; untouched slots must
 keep their poison; the page table must equal the CPU placement model; blocks sampled from the
 library's pool are decoded by the oracle and compared with the same slot bytes.
-FFN: the oracle (FP64, h rounded to BF16) is evaluated on sampled tokens, all hidden columns.
+FFN: the oracle (FP64, h rounded to BF16) is evaluated on every token and every hidden column;
+the gate is the relative Frobenius error over the whole output, and the worst single token must
+meet the same bound.
 """
 import numpy as np
 import pytest
@@ -47,7 +49,7 @@ def check_sampled_blocks_against_oracle(pool, blob, layer, ids, slots, n_samples
     assert np.array_equal(got, parts[0])
 
 
-def run_full(cfg, n_sample_tokens=3):
+def run_full(cfg):
     from gpu_common import build_pool
     print("building", cfg.name, flush=True)
     pool = None
@@ -91,28 +93,29 @@ def run_full(cfg, n_sample_tokens=3):
             pool.shared_expert_ffn(s13, s2, xd, out, B.FFN_ACCUMULATE)
         torch.cuda.synchronize()
         assert pool.device_errors() == 0
-        # FFN on sampled tokens
-        rng = np.random.default_rng(5)
-        sel = np.sort(rng.choice(cfg.tokens, n_sample_tokens, replace=False))
+        # FFN: every token, every column
         weights = lambda e: (inputs.bits_u16(w13[e]), inputs.bits_u16(w2[e]))
-        want = offn.moe_ffn(inputs.bits_u16(x)[sel], ids[sel], g[sel], weights, round_h=True)
+        xb = inputs.bits_u16(x)
+        want = offn.moe_ffn(xb, ids, g, weights, round_h=True)
         if cfg.shared_expert:
             s13h, s2h = inputs.bits_u16(s13.cpu()), inputs.bits_u16(s2.cpu())
-            n = len(sel)
-            want = want + offn.moe_ffn(inputs.bits_u16(x)[sel], np.zeros((n, 1), dtype=np.int32),
-                                       np.ones((n, 1), dtype=np.float32), lambda e: (s13h, s2h), round_h=True)
-        got = out[torch.from_numpy(sel).cuda()].cpu().numpy()
+            want = want + offn.moe_ffn(xb, np.zeros((cfg.tokens, 1), dtype=np.int32),
+                                       np.ones((cfg.tokens, 1), dtype=np.float32), lambda e: (s13h, s2h), round_h=True)
+        got = out.cpu().numpy()
+        assert np.isfinite(got).all()
         err = offn.rel_frobenius(got, want)
-        print(cfg.name, "FFN rel. Frobenius error on tokens", sel.tolist(), "= %.3e" % err, flush=True)
-        assert np.isfinite(out.cpu().numpy()).all()
+        per_token = np.linalg.norm(got - want, axis=1) / np.linalg.norm(want, axis=1)
+        print(cfg.name, "FFN rel. Frobenius error over all %d tokens = %.3e, worst token %d: %.3e"
+              % (cfg.tokens, err, int(per_token.argmax()), float(per_token.max())), flush=True)
         assert err <= TOL
+        assert float(per_token.max()) <= TOL
     finally:
         if pool is not None:
             pool.close()
 
 
 def test_c2_mixtral_shaped_layer():
-    run_full(inputs.CONFIGS["c2_mixtral"], n_sample_tokens=2)
+    run_full(inputs.CONFIGS["c2_mixtral"])
 
 
 def test_c3_qwen3next_shaped_layer_two_waves():
@@ -126,4 +129,4 @@ def test_c4_glm45_shaped_layer():
 def test_c2_mixtral_shaped_layer_prefill_batch():
     """The same layer with 1024 tokens (about 256 rows per expert): the LDS-tiled MFMA kernels at
     full size, the second product with its K split over two workgroups per tile."""
-    run_full(inputs.scaled(inputs.CONFIGS["c2_mixtral"], tokens=1024), n_sample_tokens=2)
+    run_full(inputs.scaled(inputs.CONFIGS["c2_mixtral"], tokens=1024))

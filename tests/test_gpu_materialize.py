@@ -115,6 +115,36 @@ def test_gpu_decodes_streams_written_by_the_oracle_encoder():
         pool.close()
 
 
+def test_gpu_decodes_the_hand_built_two_visit_block():
+    """The pool's second down-tensor block is, byte for byte, the hand-assembled block of
+    tests/golden/handbuilt_block_two_visits.txt (first element 3200, sub-streams 0..7 visited twice);
+    the decoded slot must hold the tensor the fixture's header states."""
+    from gpu_common import u16
+    from test_oracle_codec import handbuilt_two_visits
+    from paper_2604_02715_amd import harness
+    words, blk, e0 = handbuilt_two_visits()
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=1, hidden=8, ffn=472, n_slots=2, tokens=8, top_k=1)
+    pool = harness.ExpertPool(cfg)
+    try:
+        w2 = torch.from_numpy(words.view(np.int16).copy()).view(torch.bfloat16).reshape(1, 472, 8)
+        w13 = torch.from_numpy(np.concatenate([words, words[::-1]]).view(np.int16).copy()).view(torch.bfloat16).reshape(1, 2, 8, 472)
+        blob = pool.encode_layer(0, w13, w2)
+        assert B.fluxmoe_tensor_blocks(pool.ctx, 0, 2, 0) == (0, 2)
+        view = blob.numpy().reshape(-1, 4096)
+        assert np.array_equal(view[1], blk), "the pool does not hold the hand-built block"
+        pool.bind_layer(0, blob)
+        pool.poison_slots()
+        pool.reset_page_table()
+        pool.materialize(0, [0], [1])
+        torch.cuda.synchronize()
+        assert pool.device_errors() == 0
+        assert np.array_equal(u16(pool.slot2(1)), words)
+        assert np.array_equal(u16(pool.slot13(1)), np.concatenate([words, words[::-1]]))
+        assert (u16(pool.slot2(0)) == 0x7FC1).all()
+    finally:
+        pool.close()
+
+
 def test_oracle_decodes_the_library_pool_and_matches_the_gpu():
     from gpu_common import build_pool, u16
     cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=2, hidden=128, ffn=256, n_slots=2)

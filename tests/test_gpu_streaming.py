@@ -129,3 +129,72 @@ def test_overlapped_schedule_matches_oracle_and_single_stream_schedule(tiers):
         assert (pool.page_table.cpu().numpy() == -1).all()             # everything was released
     finally:
         pool.close()
+
+
+def test_single_layer_waves_with_release_on_another_stream():
+    """One layer, two streams, repeated passes: every wave's release runs on the inference stream
+    while the next wave's materialize (same layer, same page-table row, same slots) runs on the
+    load stream.  The release must wait for the wave's FFN and the next materialize for the
+    release, otherwise the table ends at -1 for mapped experts and the FFN silently drops them
+    (Alg. 1's ordering applied to the page-table row)."""
+    cfg = small_stream_cfg(n_layers=1, n_experts=12, n_slots=8, host_fraction=0.0)
+    pool = harness.ExpertPool(cfg)
+    try:
+        w13, w2 = harness.make_layer_on_host(cfg, 0)
+        pool.bind_layer(0, pool.encode_layer(0, w13, w2))
+        routings = [inputs.routing(cfg, 0)]
+        x_host = inputs.activations(cfg, 0)
+        outs = [torch.zeros((cfg.tokens, cfg.hidden), dtype=torch.float32, device="cuda")]
+        proxy = harness.StreamingProxy(pool, routings, [x_host.cuda()], outs)
+        assert len(proxy.plan[0][1]) >= 2                               # several waves through 4 slots
+        want = offn.moe_ffn(inputs.bits_u16(x_host), routings[0][0], routings[0][1],
+                            lambda e: (inputs.bits_u16(w13[e]), inputs.bits_u16(w2[e])), round_h=True)
+        pool.reset_page_table()
+        torch.cuda.synchronize()
+        first = None
+        for rep, delay in enumerate((0, 300000, 0, 300000)):
+            outs[0].fill_(float("nan"))
+            torch.cuda.synchronize()
+            proxy.run_pass(ffn_delay_cycles=delay)
+            proxy.run_pass(ffn_delay_cycles=delay)                      # back to back: pass 2 reuses pass 1's slots
+            torch.cuda.synchronize()
+            assert pool.device_errors() == 0
+            got = outs[0].cpu().numpy()
+            err = offn.rel_frobenius(got, want)
+            print("rep", rep, "rel. Frobenius error %.3e" % err, flush=True)
+            assert err <= 1e-3
+            if first is None:
+                first = got.copy()
+            assert np.array_equal(got, first)
+            assert (pool.page_table.cpu().numpy() == -1).all()
+    finally:
+        pool.close()
+
+
+def test_prefetch_of_some_experts_then_materialize_of_others_restages_in_order():
+    """A fetch of experts A on a side stream, then a materialize of experts outside A on another
+    stream: the materialize stages its own blocks into the same half with another layout; its copies
+    must not start before the fetch's copies have landed (they would be overwritten)."""
+    cfg = small_stream_cfg(n_layers=1, n_experts=12, n_slots=12, host_fraction=0.9)
+    pool, dense, stats = build(cfg)
+    try:
+        from gpu_common import assert_slot_equals
+        pool.poison_slots()
+        pool.reset_page_table()
+        side, main = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        for rep in range(3):
+            a_set, b_set = [0, 1, 2, 3, 4, 5, 6, 7], [8, 9, 10, 11]
+            pool.prefetch_host(0, a_set, side)
+            pool.materialize(0, b_set, [0, 1, 2, 3], main)
+            torch.cuda.synchronize()
+            assert pool.device_errors() == 0
+            for e, s in zip(b_set, [0, 1, 2, 3]):
+                assert_slot_equals(pool, s, dense[0][0][e], dense[0][1][e])
+            pool.prefetch_host(0, a_set, side)
+            pool.materialize(0, a_set, [4, 5, 6, 7, 8, 9, 10, 11], main)
+            torch.cuda.synchronize()
+            for e, s in zip(a_set, [4, 5, 6, 7, 8, 9, 10, 11]):
+                assert_slot_equals(pool, s, dense[0][0][e], dense[0][1][e])
+    finally:
+        pool.close()

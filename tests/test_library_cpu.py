@@ -171,3 +171,23 @@ def test_ffn_launch_plan_follows_rows_per_expert():
     assert plan(512, 8, n_experts=160, hidden=5120, ffn=1536, n_slots=160) == (64, 1)
     with pytest.raises(B.FluxmoeError):
         plan(16, 9)
+
+
+def test_library_encoder_reproduces_the_hand_built_two_visit_block():
+    """The C++ encoder on a one-expert layer whose down tensor is the fixture's tensor (8 x 472):
+    its second block must equal the hand-assembled bytes (tests/golden/handbuilt_block_two_visits.txt;
+    the optimal lengths are unique for this dyadic histogram, so the canonical stream is determined)."""
+    from test_oracle_codec import handbuilt_two_visits
+    words, blk, e0 = handbuilt_two_visits()
+    ctx = B.fluxmoe_create(1, 1, 8, 472, 1)
+    w2 = np.ascontiguousarray(words)
+    w13 = np.ascontiguousarray(np.concatenate([words, words[::-1]]))
+    dst = np.zeros(B.fluxmoe_query_sizes(ctx).layer_blob_bound, dtype=np.uint8)
+    used = B.fluxmoe_encode_pool(ctx, 0, w13.ctypes.data, w2.ctypes.data, dst.ctypes.data, dst.size, 2)
+    assert B.fluxmoe_tensor_blocks(ctx, 0, 2, 0) == (0, 2)
+    assert list(B.fluxmoe_tensor_first_elems(ctx, 0, 2, 0)) == [0, 3200, 3776]
+    lens = B.fluxmoe_code_lengths(ctx, 0, 2)
+    assert [int(lens[s]) for s in (0x78, 0x79, 0x7A, 0x7B)] == [1, 2, 3, 3] and int(lens.sum()) == 9
+    assert np.array_equal(dst[4096:8192], blk)
+    assert used % 4096 == 0
+    B.fluxmoe_destroy(ctx)

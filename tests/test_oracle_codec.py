@@ -184,6 +184,52 @@ def test_handbuilt_block_decodes_bit_by_bit_and_encoder_reproduces_it():
     assert list(first) == [0, 64] and np.array_equal(blocks[0], blk)
 
 
+def handbuilt_two_visits():
+    """(whole tensor of 3776 words, the hand-assembled second block, its first element index):
+    tests/golden/handbuilt_block_two_visits.txt.  The tensor is restated here from the rule the
+    fixture's header states."""
+    A, Bx, Cx, D = 0x78, 0x79, 0x7A, 0x7B
+    p1 = [A, Bx, A, Cx, A, Bx, A, D]
+    p2 = [D, Cx, Bx, Bx, A, A, A, A]
+    words = np.zeros(3776, dtype=np.uint16)
+    for g in range(3776):
+        e = (p1 if g // 8 < 464 else p2)[g % 8]
+        sm = g % 256
+        words[g] = ((sm & 0x80) << 8) | (e << 7) | (sm & 0x7F)
+    fields = {}
+    for line in open(os.path.join(HERE, "golden", "handbuilt_block_two_visits.txt")):
+        if line.startswith("#") or ":" not in line:
+            continue
+        k, v = line.split(":", 1)
+        fields[k.strip()] = np.frombuffer(bytes.fromhex(v.strip().replace(" ", "")), dtype=np.uint8)
+    assert fields["sub_bits"].size == 128 and fields["sm"].size == 576 and fields["code"].size == 126
+    blk = np.zeros(4096, dtype=np.uint8)
+    blk[0:8] = fields["n_e0"]
+    blk[8:136] = fields["sub_bits"]
+    blk[136:712] = fields["sm"]
+    blk[712:712 + 126] = fields["code"]
+    return words, blk, 3200
+
+
+def test_handbuilt_block_with_two_visits_and_nonzero_first_element():
+    """Sub-streams 0..7 are visited twice (elements 512..575 of the block continue them), sub-streams
+    8..63 once, and the block starts at element 3200 of its tensor: a decoder that sends the second
+    visit to the wrong sub-stream, restarts a sub-stream instead of continuing it, or ignores e0
+    fails here against typed-in bytes."""
+    words, blk, e0_want = handbuilt_two_visits()
+    lens = np.zeros(256, dtype=np.uint8)
+    lens[[0x78, 0x79, 0x7A, 0x7B]] = (1, 2, 3, 3)                # typed in, not computed
+    e0, out = codec.decode_block_bitwise(blk, lens)
+    assert e0 == e0_want and np.array_equal(out, words[3200:])
+    e0s, ns, outs = codec.decode_blocks(blk, lens)
+    assert e0s[0] == e0_want and ns[0] == 576 and np.array_equal(outs[0], words[3200:])
+    computed = codec.code_lengths(codec.exponent_histogram(words))
+    assert np.array_equal(computed, lens)
+    blocks, first = codec.encode_tensor(words, computed)
+    assert list(first) == [0, 3200, 3776] and np.array_equal(blocks[1], blk)
+    assert np.array_equal(codec.decode_tensor(blocks, lens, 3776), words)
+
+
 def test_corrupt_streams_are_rejected():
     words, blk = handbuilt()
     lens = np.zeros(256, dtype=np.uint8)
