@@ -255,6 +255,26 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* ctx, uint32_t layer, const uint16_t* tokens,
                        const int32_t* page_table, float* out, uint32_t flags, void* stream);
 
 /*
+ * fluxmoe_expert_ffn for callers that cannot allocate or bring a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, same result, same
+ * event protocol, but the FFN scratch (pair order, tile list, the SwiGLU product h, split-K partials)
+ * lives in a static device array of FLUXMOE_STATIC_SCRATCH_BYTES bytes that is part of the loaded
+ * library (every GPU the library runs on holds its own copy until the process ends) instead of the
+ * bound workspace.  The call itself allocates nothing and frees nothing; the array's device address
+ * is resolved by fluxmoe_bind_arenas, which must have run on the current device.
+ *   ENOMEM  T, K need more scratch than FLUXMOE_STATIC_SCRATCH_BYTES (fluxmoe_ffn_workspace_bytes
+ *           gives the need); nothing is enqueued
+ *   ESTATE  the current device is not the one fluxmoe_bind_arenas ran on
+ * Every call on a GPU shares that GPU's array, whatever the context: calls that overlap on one GPU
+ * (two streams, two contexts, two threads) race on it and must be ordered by the caller.  Nothing
+ * in the array has to start at zero: every call rewrites each part before reading it.
+ */
+#define FLUXMOE_STATIC_SCRATCH_BYTES (32ull << 20)
+int fluxmoe_expert_ffn_static(fluxmoe_ctx* ctx, uint32_t layer, const uint16_t* tokens, uint32_t T,
+                              const int32_t* topk_ids, const float* topk_w, uint32_t K,
+                              const int32_t* page_table, float* out, uint32_t flags, void* stream);
+
+/*
  * The shared expert of a layer (Sec. 3 excludes shared experts from the routed set; Sec. 4.2
  * keeps their weights uncompressed and GPU resident): the same SwiGLU FFN applied to every
  * token with gate 1, on dense weights the caller keeps resident.

@@ -97,6 +97,9 @@ EXPORTS = {
     "fluxmoe_expert_ffn": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
                                      C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
                                      C.c_void_p]),
+    "fluxmoe_expert_ffn_static": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
+                                            C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
+                                            C.c_void_p]),
     "fluxmoe_shared_expert_ffn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                             C.c_void_p, C.c_uint32, C.c_void_p]),
     "fluxmoe_stream_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]),
@@ -256,6 +259,15 @@ def fluxmoe_expert_ffn(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K, p
                        out_ptr, flags=0, stream=None):
     _check(lib().fluxmoe_expert_ffn(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K,
                                     page_table_ptr, out_ptr, flags, stream))
+
+
+STATIC_SCRATCH_BYTES = 32 << 20          # FLUXMOE_STATIC_SCRATCH_BYTES
+
+
+def fluxmoe_expert_ffn_static(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K, page_table_ptr,
+                              out_ptr, flags=0, stream=None):
+    _check(lib().fluxmoe_expert_ffn_static(ctx, layer, tokens_ptr, T, topk_ids_ptr, topk_w_ptr, K,
+                                           page_table_ptr, out_ptr, flags, stream))
 
 
 def fluxmoe_shared_expert_ffn(ctx, w13_ptr, w2_ptr, tokens_ptr, T, out_ptr, flags=0, stream=None):

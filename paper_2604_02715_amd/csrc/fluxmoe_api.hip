@@ -61,8 +61,18 @@ struct FfnPlan {
 inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 }  // namespace
 
+// FFN scratch of fluxmoe_expert_ffn_static: one array per GPU, part of the loaded code object, held until
+// the process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the device
+// address of each GPU's copy is resolved once per device (resolve_static_scratch, called by
+// fluxmoe_bind_arenas with that device current) and kept in g_static_scratch.
+constexpr uint64_t kStaticScratchBytes = FLUXMOE_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) uint8_t scratch[kStaticScratchBytes];
+static uint8_t* g_static_scratch[kMaxDevices] = {};
+
 struct fluxmoe_ctx {
     fluxmoe_desc d;
+    int device = -1;                      // HIP device the arenas were bound on
     uint64_t elems13 = 0, elems2 = 0;
     std::vector<LayerMeta> layers;
     // arenas
@@ -250,6 +260,16 @@ int ensure_events(fluxmoe_ctx* c) {
     HIPCHECK(hipHostMalloc(reinterpret_cast<void**>(&c->pinned_cmd), size_t(kRing) * c->cmd_bytes,
                            hipHostMallocDefault));
     c->events_ready = true;
+    return FLUXMOE_OK;
+}
+
+int resolve_static_scratch(int dev) {
+    if (dev < 0 || dev >= kMaxDevices) return set_error(FLUXMOE_EHIP, "device index %d out of range", dev);
+    if (g_static_scratch[dev]) return FLUXMOE_OK;
+    void* ptr = nullptr;
+    HIPCHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return set_error(FLUXMOE_EHIP, "hipGetSymbolAddress returned a NULL address");
+    g_static_scratch[dev] = static_cast<uint8_t*>(ptr);
     return FLUXMOE_OK;
 }
 
@@ -538,6 +558,8 @@ int fluxmoe_bind_arenas(fluxmoe_ctx* c, void* slots13, void* slots2, void* works
     if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
         return set_error(FLUXMOE_EHIP, "device is %s; this library is built for gfx950 only", prop.gcnArchName);
     c->n_cus = prop.multiProcessorCount;
+    if (int rc = resolve_static_scratch(dev)) return rc;
+    c->device = dev;
     if (int rc = ensure_events(c)) return rc;
     c->slots13 = static_cast<uint8_t*>(slots13);
     c->slots2 = static_cast<uint8_t*>(slots2);
@@ -925,7 +947,7 @@ int fluxmoe_release(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, u
     return FLUXMOE_OK;
 }
 
-// Body of fluxmoe_expert_ffn: `w` is the FFN scratch (pair order, tile
+// Shared body of fluxmoe_expert_ffn and fluxmoe_expert_ffn_static: `w` is the FFN scratch (pair order, tile
 // list, h, split-K partials) of `w_bytes` bytes, `w_name` says where it comes from in error texts.
 static int expert_ffn_enqueue(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, uint32_t T,
                               const int32_t* topk_ids, const float* topk_w, uint32_t K,
@@ -986,6 +1008,22 @@ int fluxmoe_expert_ffn(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, u
     if (T == 0) return FLUXMOE_OK;
     return expert_ffn_enqueue(c, layer, tokens, T, topk_ids, topk_w, K, page_table, out, flags, stream_v,
                               c->ws + c->pool_ws_bytes, c->ws_bytes - c->pool_ws_bytes, "the bound workspace past the pool part");
+}
+
+int fluxmoe_expert_ffn_static(fluxmoe_ctx* c, uint32_t layer, const uint16_t* tokens, uint32_t T,
+                              const int32_t* topk_ids, const float* topk_w, uint32_t K,
+                              const int32_t* page_table, float* out, uint32_t flags, void* stream_v) {
+    if (int rc = check_layer(c, layer, false)) return rc;
+    if (!c->arenas_bound) return set_error(FLUXMOE_ESTATE, "fluxmoe_bind_arenas has not been called");
+    if (T == 0) return FLUXMOE_OK;
+    uint8_t* w = (c->device >= 0 && c->device < kMaxDevices) ? g_static_scratch[c->device] : nullptr;
+    if (!w) return set_error(FLUXMOE_ESTATE, "the static scratch of device %d was not resolved at bind time", c->device);
+    int dev = -1;
+    HIPCHECK(hipGetDevice(&dev));
+    if (dev != c->device)
+        return set_error(FLUXMOE_ESTATE, "current device is %d, the context was bound on device %d", dev, c->device);
+    return expert_ffn_enqueue(c, layer, tokens, T, topk_ids, topk_w, K, page_table, out, flags, stream_v,
+                              w, kStaticScratchBytes, "the static FFN scratch");
 }
 
 int fluxmoe_shared_expert_ffn(fluxmoe_ctx* c, const uint16_t* w13, const uint16_t* w2,
