@@ -106,10 +106,9 @@ struct fluxmoe_ctx {
     hipEvent_t ev_half_done[2] = {};        // last decode that read the half
     bool half_done_valid[2] = {false, false};
     bool copied_valid[2] = {false, false};  // ev_copied[h] has been recorded
-    // launch shape of the decode kernel (FLUXMOE_DECODE_WAVES / FLUXMOE_DECODE_WG_PER_CU override)
+    // launch shape of the decode kernel (FLUXMOE_DECODE_WAVES / FLUXMOE_DECODE_BLOCKS_PER_WAVE override)
     int tune_waves = 8;
-    int tune_wg_per_cu = 64;
-    int tune_chunk = 1;
+    int tune_blocks_per_wave = 3;
     int tune_tiled_waves = 2;             // FLUXMOE_FFN_TILED_WAVES: 2 = LDS-direct loads (default), 8 = register-staged,
                                           // 4 = register-staged with four wavefronts of 128 x 128
     // optional kernel timing (fluxmoe_profile_*)
@@ -213,21 +212,44 @@ FfnPlan plan_ffn(const FfnShape& c, uint32_t T, uint32_t K) {
     return p;
 }
 
+// Pair table of the decode kernel, indexed by the next 12 stream bits (first stream bit in bit 0).
+// Entry: bits 0..5 bits to advance, 7..14 first exponent, 15..18 length of the first code, 23..30
+// second exponent, bit 31 set when the second code does not end inside the 12 bits (the entry then
+// covers the first symbol only).  Bit patterns no code matches (only possible with a single used
+// symbol) decode as the first used symbol with length 1: valid streams never reach them.
 void build_lut(const uint8_t lens[256], uint32_t* lut) {
     uint16_t codes[256];
     canonical_codes(lens, codes);
     int fallback = -1;
     for (int s = 0; s < 256; ++s)
         if (lens[s]) { fallback = s; break; }
-    const uint32_t fill = fallback < 0 ? 1u : ((uint32_t(fallback) << 23) | 1u);
-    for (uint32_t i = 0; i < kLutEntries; ++i) lut[i] = fill;
+    // single-symbol table: 12 stream bits -> (symbol, length)
+    std::vector<uint16_t> one(kLutEntries, uint16_t(fallback < 0 ? 1 : ((fallback << 4) | 1)));
     for (int s = 0; s < 256; ++s) {
         const uint32_t L = lens[s];
         if (!L || L > kLutBits) continue;
         uint32_t rev = 0;   // first code bit in bit 0: that is how the stream is peeked
         for (uint32_t b = 0; b < L; ++b) rev |= ((codes[s] >> (L - 1 - b)) & 1u) << b;
         for (uint32_t hi = 0; hi < (1u << (kLutBits - L)); ++hi)
-            lut[rev | (hi << L)] = (uint32_t(s) << 23) | L;
+            one[rev | (hi << L)] = uint16_t((s << 4) | L);
+    }
+    for (uint32_t i = 0; i < kLutEntries; ++i) {
+        const uint32_t s0 = one[i] >> 4, l0 = one[i] & 15u;
+        uint32_t entry = 0x80000000u | (l0 << 15) | (s0 << 7) | l0;
+        if (l0 < kLutBits) {
+            // the second code must end inside the remaining 12 - l0 bits; the bits above them are zero
+            // in this index, so a match longer than what remains is not a match
+            const uint32_t rest = i >> l0;
+            const uint32_t s1 = one[rest] >> 4, l1 = one[rest] & 15u;
+            bool real = false;                      // is `rest` really the code of s1, not the fallback?
+            if (lens[s1] == l1) {
+                uint32_t rev = 0;
+                for (uint32_t b = 0; b < l1; ++b) rev |= ((codes[s1] >> (l1 - 1 - b)) & 1u) << b;
+                real = (rest & ((1u << l1) - 1u)) == rev;
+            }
+            if (real && l0 + l1 <= kLutBits) entry = (s1 << 23) | (l0 << 15) | (s0 << 7) | (l0 + l1);
+        }
+        lut[i] = entry;
     }
 }
 
@@ -336,13 +358,9 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
         const int w = std::atoi(v);
         if (w == 4 || w == 8 || w == 16) c->tune_waves = w;
     }
-    if (const char* v = std::getenv("FLUXMOE_DECODE_CHUNK")) {
+    if (const char* v = std::getenv("FLUXMOE_DECODE_BLOCKS_PER_WAVE")) {
         const int w = std::atoi(v);
-        if (w >= 1 && w <= (1 << 20)) c->tune_chunk = w;
-    }
-    if (const char* v = std::getenv("FLUXMOE_DECODE_WG_PER_CU")) {
-        const int w = std::atoi(v);
-        if (w >= 1 && w <= 1024) c->tune_wg_per_cu = w;
+        if (w >= 1 && w <= 1024) c->tune_blocks_per_wave = w;
     }
     if (const char* v = std::getenv("FLUXMOE_FFN_TILED_WAVES")) {
         const int w = std::atoi(v);
@@ -882,12 +900,12 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
         if (!touched.empty())
             HIPCHECK(launch_apply_updates(page_table, dcmd + upd_off, uint32_t(touched.size()), stream));
     } else {
-    uint32_t n_wg = uint32_t(std::min<uint64_t>(uint64_t(c->n_cus) * c->tune_wg_per_cu, (total + waves_per_wg - 1) / waves_per_wg));
+    const uint64_t per_wg = uint64_t(waves_per_wg) * c->tune_blocks_per_wave;
+    uint32_t n_wg = uint32_t(std::min<uint64_t>((total + per_wg - 1) / per_wg, 1u << 20));
     n_wg = std::max(n_wg, 2u);
     uint32_t split = uint32_t((uint64_t(n_wg) * cmd->total_blocks[1] + total / 2) / total);
     split = std::min(std::max(split, 1u), n_wg - 1);
     args.wg_split = split;
-    args.chunk_blocks = uint32_t(c->tune_chunk);
     HIPCHECK(span_begin(c, 0, stream));
     HIPCHECK(launch_decode(args, n_wg, waves_per_wg, stream));
     HIPCHECK(span_end(c, stream));
