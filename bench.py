@@ -189,12 +189,17 @@ def main():
     ffn_ms = sum(prof[k][0] for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")) / n_break
     achieved = (comp_bytes + dense_bytes) / (decode_step_ms * 1e-3) / 1e9
 
-    traffic = None
+    # HBM bytes per launch from hardware counters (two rocprofv3 --pmc runs, summarised in profiles/): only
+    # valid for the kernel source they were measured on, so the record carries a hash of that source and a
+    # record taken on another version of the kernel is not reported
+    traffic, traffic_note = None, None
     tpath = os.path.join(ROOT, "profiles", "decode_traffic.json")
     if os.path.exists(tpath):
         rec = json.load(open(tpath))
-        if rec.get("workload") == cfg.name:
-            traffic = rec.get("hbm_bytes_per_launch")
+        if rec.get("kernel_source_sha256") != decode_kernel_source_hash():
+            traffic_note = "profiles/decode_traffic.json was measured on another version of the decode kernel"
+        elif cfg.name in rec.get("workloads", {}):
+            traffic = rec["workloads"][cfg.name].get("hbm_bytes_per_launch")
 
     result = {
         "metric": "expert_materialization_dense_out",
@@ -215,7 +220,8 @@ def main():
                    "step": "materialize + expert FFN on one stream" + (" per wave of n_slots experts, then release" if len(waves) > 1 else "")},
         "roofline": {"kernel": "decode_kernel", "bound": "hbm", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic, "algorithmic_bytes_per_launch": (comp_bytes + dense_bytes) // n_launch,
+                     "traffic": traffic, **({"traffic_note": traffic_note} if traffic_note else {}),
+                     "algorithmic_bytes_per_launch": (comp_bytes + dense_bytes) // n_launch,
                      "launches_per_step": n_launch, "avg_launch_ms": round(decode_ms, 4)},
         "materialize": {"dense_out_GBps": round(dense_bytes / (decode_step_ms * 1e-3) / 1e9, 1),
                         "compressed_bytes": comp_bytes, "dense_bytes": dense_bytes,
@@ -236,8 +242,21 @@ def main():
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(pool, cfg, blob, w13, w2, args.cpu_seconds)
+        try:
+            result["cpu_baseline"]["expert_ffn"] = cpu_baseline_ffn(cfg, x.cpu(), ids_np, g_np, w13, w2)
+        except Exception as exc:                                  # the decode figure stands on its own
+            result["cpu_baseline"]["expert_ffn"] = {"error": str(exc)[:200]}
     print(json.dumps(result), flush=True)
     pool.close()
+
+
+def decode_kernel_source_hash():
+    """sha256 over the sources the decode kernel is compiled from."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("decode_kernel.hip", "kernels.h"):
+        h.update(open(os.path.join(ROOT, "paper_2604_02715_amd", "csrc", name), "rb").read())
+    return h.hexdigest()
 
 
 def bench_exp3(args):
@@ -617,8 +636,11 @@ def bench_streaming(cfg, args):
                           "pass_ms_over_layers": round(float(whole.mean()) / cfg.n_layers, 3),
                           "host_fetch_ms_isolated": round(copy_ms, 3), "decode_ms_isolated": round(decode_ms, 3),
                           "ffn_ms_isolated": round(ffn_ms, 3), "pcie_GBps": pcie_rate,
-                          "overlap_efficiency": (round(max(copy_ms, decode_ms + ffn_ms) / per_layer_ms, 3)
-                                                 if placement != "whole_layer" else None),
+                          # the longer of the two isolated legs over the measured steady-state time: 1.0 means the
+                          # per-layer time equals its longest leg (the other one is fully hidden behind it); with no
+                          # host tier the longest leg is decode + FFN back to back, so the ratio says nothing about overlap
+                          "longest_leg_over_measured": (round(max(copy_ms, decode_ms + ffn_ms) / per_layer_ms, 3)
+                                                        if placement != "whole_layer" else None),
                           "dense_out_GBps": round(dense_bytes / (per_layer_ms * 1e-3) / 1e9, 1)},
             "setup_s": round(setup_s + (t1 - t0 if placement == placements[0] else 0), 1),
         }
@@ -658,6 +680,36 @@ def cpu_baseline(pool, cfg, blob, w13, w2, budget_s):
         res["all_cores"] = cpu_baseline_all_cores(pool, cfg, blocks, w2, max(1, tensors))
     except Exception as exc:                                  # the single-thread figure stands on its own
         res["all_cores"] = {"error": str(exc)[:200]}
+    return res
+
+
+def cpu_baseline_ffn(cfg, x, ids_np, g_np, w13, w2):
+    """The FP64 FFN oracle, as it stands (oracle/ffn.moe_ffn, h rounded to BF16), on a bounded sample of the
+    same batch: every (token, k) pair routed to the busiest expert, i.e. one expert's whole row group.  Timed
+    with one BLAS thread and with all host threads; the time includes the oracle's widening of the expert's
+    BF16 weights to FP64.  FLOPs = 6 H F per pair."""
+    import numpy as np
+    from oracle import ffn as offn
+    from paper_2604_02715_amd import inputs
+    import threadpoolctl
+
+    counts = np.bincount(ids_np.reshape(-1), minlength=cfg.n_experts)
+    e = int(counts.argmax())
+    pairs = int(counts[e])
+    xb = inputs.bits_u16(x)
+    weights = lambda k: (inputs.bits_u16(w13[k]), inputs.bits_u16(w2[k]))
+    flops = 6.0 * cfg.hidden * cfg.ffn * pairs
+    res = {"unit": "TFLOP/s", "kind": "oracle",
+           "sample": "oracle/ffn.moe_ffn (FP64, h rounded to BF16) on the %d pairs routed to expert %d of this batch, "
+                     "%.2f GFLOP, weight widening included" % (pairs, e, flops / 1e9)}
+    for label, limit in (("one_thread", 1), ("all_threads", None)):
+        with threadpoolctl.threadpool_limits(limits=limit):
+            t0 = time.perf_counter()
+            out = offn.moe_ffn(xb, ids_np, g_np, weights, round_h=True, mapped={e})
+            dt = time.perf_counter() - t0
+            threads = 1 if limit == 1 else max(info["num_threads"] for info in threadpoolctl.threadpool_info() or [{"num_threads": os.cpu_count()}])
+        assert np.isfinite(out).all()
+        res[label] = {"value": round(flops / dt / 1e12, 6), "cores": int(threads), "seconds": round(dt, 2)}
     return res
 
 
