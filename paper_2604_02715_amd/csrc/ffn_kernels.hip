@@ -141,8 +141,6 @@ __device__ __forceinline__ uint32_t comp(const uint4& v, int i) {
 
 // k chunks per wavefront held in the register ring (one being multiplied, the rest in flight)
 template <int MI> struct RingDepth { static constexpr int value = MI >= 8 ? 2 : (MI >= 4 ? 3 : 4); };
-// the smaller body a kernel for tiles of 16 MI rows also carries (for tiles with few rows)
-template <int MI> struct SmallerBody { static constexpr int value = MI == 6 ? 4 : (MI >= 2 ? MI / 2 : 1); };   // 8 -> 4
 
 // Shared A blocks: the four wavefronts of a workgroup multiply the same rows of A, so a block of
 // kABlock k values of the tile's rows is loaded once per workgroup into LDS (two buffers) instead of
@@ -462,9 +460,9 @@ __device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileIn
         }
 }
 
-// Row tiles hold up to 16 MI rows, sized with headroom over the mean rows per expert so that an
-// expert's weights are streamed once; tiles with few rows take a body compiled for fewer 16-row
-// MFMA tiles (less work per chunk, same registers reserved).
+// Row tiles hold up to 16 MI rows so that an expert's weights are streamed once even when routing is
+// skewed (an expert with 231 of 2560 pairs next to hundreds with five); a tile with fewer rows takes a
+// body compiled for fewer 16-row MFMA tiles (less matrix work per chunk, same registers reserved).
 template <int MI>
 __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
     // the accumulator exchange of the epilogue ([pair][mi, c, r][lane] floats) reuses the memory of
@@ -476,8 +474,10 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
     uint16_t* abuf = reinterpret_cast<uint16_t*>(smem);
     TileInfo t;
     if (!tile_info(a, blockIdx.y, t)) return;     // uniform over the workgroup
-    constexpr int kSmall = SmallerBody<MI>::value;
-    if (kSmall < MI && t.rows <= 16 * kSmall) gemm1_swiglu_body<kSmall>(a, t, xch, abuf);
+    if (MI > 1 && t.rows <= 16) gemm1_swiglu_body<1>(a, t, xch, abuf);
+    else if (MI > 2 && t.rows <= 32) gemm1_swiglu_body<2>(a, t, xch, abuf);
+    else if (MI > 4 && t.rows <= 64) gemm1_swiglu_body<4>(a, t, xch, abuf);
+    else if (MI > 6 && t.rows <= 96) gemm1_swiglu_body<6>(a, t, xch, abuf);
     else gemm1_swiglu_body<MI>(a, t, xch, abuf);
 }
 
@@ -538,8 +538,10 @@ __global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
     __shared__ __align__(16) uint16_t abuf[2 * StripGemm<MI>::kABufElems];
     TileInfo t;
     if (!tile_info(a, blockIdx.y, t)) return;
-    constexpr int kSmall = SmallerBody<MI>::value;
-    if (kSmall < MI && t.rows <= 16 * kSmall) gemm2_body<kSmall>(a, t, abuf);
+    if (MI > 1 && t.rows <= 16) gemm2_body<1>(a, t, abuf);
+    else if (MI > 2 && t.rows <= 32) gemm2_body<2>(a, t, abuf);
+    else if (MI > 4 && t.rows <= 64) gemm2_body<4>(a, t, abuf);
+    else if (MI > 6 && t.rows <= 96) gemm2_body<6>(a, t, abuf);
     else gemm2_body<MI>(a, t, abuf);
 }
 

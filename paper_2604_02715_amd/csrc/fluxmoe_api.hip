@@ -151,15 +151,14 @@ FfnPlan plan_ffn(const FfnShape& c, uint32_t T, uint32_t K) {
     const uint64_t groups = std::max<uint64_t>(1, std::min<uint64_t>(E, pairs));
     const uint64_t avg = (pairs + groups - 1) / groups;
     // Row tile of the weight-streaming kernels: every extra tile of an expert streams that expert's
-    // weights again, so the tile is the smallest one that an expert's row count (taken as normal
-    // with mean and variance avg, a Poisson count) exceeds with probability <= 2 %.  When even 128
-    // rows do not meet that, 128-row tiles stay the choice while the expected number of passes per
-    // expert is below 1.6 - what one pass of the LDS-tiled MFMA kernels (256-row tiles, k extents
-    // that are multiples of 64) costs relative to a streaming pass at these sizes.
+    // weights again, and routing can be far from even, so tiles hold up to 128 rows (the kernel takes a
+    // cheaper body for tiles with fewer rows).  With so many rows per expert that even 128-row tiles are
+    // exceeded often (an expert's row count taken as normal with mean and variance avg), 128-row tiles
+    // stay the choice while the expected number of passes per expert is below 1.6 - what one pass of
+    // the LDS-tiled MFMA kernels (256-row tiles, k extents that are multiples of 64) costs relative to
+    // a streaming pass at these sizes.
     auto p_over = [&](double m) { return 0.5 * std::erfc((m + 0.5 - double(avg)) / std::sqrt(2.0 * double(avg))); };
     p.m_tile = 128;
-    for (uint32_t m : {16u, 32u, 64u, 96u, 128u})
-        if (p_over(m) <= 0.02) { p.m_tile = m; break; }
     if (p_over(128) > 0.02 && 1.0 + p_over(128) + p_over(256) + p_over(384) > 1.6 && H % 64 == 0 && F % 64 == 0)
         p.m_tile = 256;
     if (const char* v = std::getenv("FLUXMOE_FFN_MTILE")) {

@@ -145,10 +145,10 @@ def test_argument_validation_on_the_host():
 
 
 def test_ffn_launch_plan_follows_rows_per_expert():
-    """Host logic of fluxmoe_expert_ffn: the row tile is the smallest one an expert's (Poisson) row count
-    rarely exceeds, 128-row tiles are kept while fewer than 1.6 passes per expert are expected, beyond
-    that the LDS-tiled kernels (256) take over; the second product is split over K so that the launch
-    fills whole rounds of the 256 CUs assumed before a device has been queried."""
+    """Host logic of fluxmoe_expert_ffn: the weight-streaming kernels take row tiles of up to 128 rows (routing
+    may be skewed; the kernels pick a cheaper body for tiles with few rows), kept while fewer than 1.6 passes
+    per expert are expected; beyond that the LDS-tiled kernels (256) take over; the second product is split
+    over K so that the launch fills whole rounds of the 256 CUs assumed before a device has been queried."""
     def plan(tokens, top_k, **kw):
         args = dict(n_layers=1, n_experts=8, hidden=4096, ffn=14336, n_slots=8)
         args.update(kw)
@@ -157,8 +157,8 @@ def test_ffn_launch_plan_follows_rows_per_expert():
             return B.fluxmoe_ffn_plan(ctx, tokens, top_k)
         finally:
             B.fluxmoe_destroy(ctx)
-    assert plan(256, 2) == (96, 4)                    # Mixtral-shaped decode batch: 64 rows per expert, one round of 256 workgroups
-    assert plan(1, 1)[0] == 16 and plan(64, 2)[0] == 32 and plan(128, 2)[0] == 64
+    assert plan(256, 2) == (128, 4)                   # Mixtral-shaped decode batch: 64 rows per expert, one round of 256 workgroups
+    assert plan(1, 1)[0] == 128 and plan(64, 2)[0] == 128 and plan(128, 2)[0] == 128
     assert plan(340, 2)[0] == 128                     # 85 rows per expert
     assert plan(512, 2)[0] == 128                     # 128 rows per expert: about 1.5 passes expected
     assert plan(560, 2)[0] == 256                     # 140 rows per expert: the tiled kernels are cheaper
@@ -167,8 +167,8 @@ def test_ffn_launch_plan_follows_rows_per_expert():
     # shapes the tiled kernels cannot take (k extents not multiples of 64) stay on 128-row tiles
     assert plan(1024, 2, hidden=4104, ffn=14344)[0] == 128
     # many small experts: one round is already full, no split
-    assert plan(256, 10, n_experts=512, hidden=2048, ffn=512, n_slots=256) == (16, 1)
-    assert plan(512, 8, n_experts=160, hidden=5120, ffn=1536, n_slots=160) == (64, 1)
+    assert plan(256, 10, n_experts=512, hidden=2048, ffn=512, n_slots=256) == (128, 1)
+    assert plan(512, 8, n_experts=160, hidden=5120, ffn=1536, n_slots=160) == (128, 1)
     with pytest.raises(B.FluxmoeError):
         plan(16, 9)
 
