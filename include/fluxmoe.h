@@ -216,6 +216,20 @@ int fluxmoe_materialize(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_
                         void* stream);
 
 /*
+ * fluxmoe_materialize with the two tensor types decoded on two streams, the stream layout of the paper's
+ * loading path (Sec. 5 "Expert memory backends" and Sec. 6.3 Exp#3: separate streams for the fused
+ * gate/up tensors and the down tensors, the latency of a layer counted from issue until both types are
+ * ready).  Waits, command upload and the type-1 launch go to `stream`, the type-2 launch to
+ * `stream_type2` after them; `stream` then waits for the type-2 launch and records the layer's load
+ * event, so everything that holds after fluxmoe_materialize's event holds after this one.  The caller
+ * must not reuse `stream_type2` for work that has to precede this call.  stream_type2 == stream is
+ * fluxmoe_materialize.
+ */
+int fluxmoe_materialize_two_streams(fluxmoe_ctx* ctx, uint32_t layer, const int32_t* expert_ids,
+                                    uint32_t n, int32_t* page_table, const int32_t* dst_slots,
+                                    void* stream, void* stream_type2);
+
+/*
  * Release experts of one layer (Sec. 3 "Expert paging": once a layer's MoE block has run, the
  * forward proxy gives that layer's expert set back): enqueue page_table[layer][e] = -1 for the
  * listed experts that are mapped; their slots become free for reuse (a later materialize into

@@ -93,6 +93,8 @@ EXPORTS = {
     "fluxmoe_prefetch_host": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p]),
     "fluxmoe_materialize": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
                                       C.c_void_p, C.c_void_p]),
+    "fluxmoe_materialize_two_streams": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
+                                                  C.c_void_p, C.c_void_p, C.c_void_p]),
     "fluxmoe_release": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p]),
     "fluxmoe_expert_ffn": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.c_void_p,
                                      C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_uint32,
@@ -245,6 +247,14 @@ def fluxmoe_materialize(ctx, layer, expert_ids, page_table_ptr, dst_slots, strea
         raise ValueError("expert_ids and dst_slots differ in length")
     _check(lib().fluxmoe_materialize(ctx, layer, ids.ctypes.data, ids.size, page_table_ptr,
                                      slots.ctypes.data, stream))
+
+
+def fluxmoe_materialize_two_streams(ctx, layer, expert_ids, page_table_ptr, dst_slots, stream, stream_type2):
+    ids, slots = _i32(expert_ids), _i32(dst_slots)
+    if ids.size != slots.size:
+        raise ValueError("expert_ids and dst_slots differ in length")
+    _check(lib().fluxmoe_materialize_two_streams(ctx, layer, ids.ctypes.data, ids.size, page_table_ptr,
+                                                 slots.ctypes.data, stream, stream_type2))
 
 
 def fluxmoe_release(ctx, layer, expert_ids, page_table_ptr, stream=None):

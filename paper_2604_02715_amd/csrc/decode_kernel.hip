@@ -181,7 +181,7 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(DecodeArgs a) {
     const DecodeCmd* cmd = a.cmd;
 
     // page-table updates ride along with the first workgroup
-    if (blockIdx.x == 0) {
+    if (blockIdx.x == 0 && a.apply_updates) {
         const uint32_t n_upd = cmd->n_pt_updates;
         const int2* upd = reinterpret_cast<const int2*>(reinterpret_cast<const char*>(cmd) +
                                                         a.upd_offset);

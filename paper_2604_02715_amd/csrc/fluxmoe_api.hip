@@ -103,6 +103,7 @@ struct fluxmoe_ctx {
     size_t staging_bytes = 0;
     StageHalf half[2];                      // layer l stages into half l & 1
     hipEvent_t ev_copied[2] = {};           // copies into the half have completed
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;   // fluxmoe_materialize_two_streams
     hipEvent_t ev_half_done[2] = {};        // last decode that read the half
     bool half_done_valid[2] = {false, false};
     bool copied_valid[2] = {false, false};  // ev_copied[h] has been recorded
@@ -274,6 +275,8 @@ int ensure_events(fluxmoe_ctx* c) {
     }
     for (int i = 0; i < kRing; ++i)
         HIPCHECK(hipEventCreateWithFlags(&c->ring_ev[i], hipEventDisableTiming));
+    HIPCHECK(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+    HIPCHECK(hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming));
     for (int i = 0; i < 2; ++i) {
         HIPCHECK(hipEventCreateWithFlags(&c->ev_half_done[i], hipEventDisableTiming));
         HIPCHECK(hipEventCreateWithFlags(&c->ev_copied[i], hipEventDisableTiming));
@@ -379,6 +382,8 @@ int fluxmoe_destroy(fluxmoe_ctx* c) {
         for (int i = 0; i < kRing; ++i) if (c->ring_ev[i]) (void)hipEventDestroy(c->ring_ev[i]);
         for (int i = 0; i < 2; ++i) if (c->ev_half_done[i]) (void)hipEventDestroy(c->ev_half_done[i]);
         for (int i = 0; i < 2; ++i) if (c->ev_copied[i]) (void)hipEventDestroy(c->ev_copied[i]);
+        if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+        if (c->ev_join) (void)hipEventDestroy(c->ev_join);
         if (c->pinned_cmd) (void)hipHostFree(c->pinned_cmd);
     }
     delete c;
@@ -757,8 +762,12 @@ int fluxmoe_prefetch_host(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_
     return stage_host_blocks(c, layer, expert_ids, n, static_cast<hipStream_t>(copy_stream));
 }
 
-int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, uint32_t n,
-                        int32_t* page_table, const int32_t* dst_slots, void* stream_v) {
+// Body of fluxmoe_materialize and fluxmoe_materialize_two_streams.  two_streams: the down tensors (type 2) are
+// decoded on stream2_v while the fused gate/up tensors (type 1) are decoded on stream_v; stream_v waits for
+// both before it records the layer's load event.
+static int materialize_enqueue(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, uint32_t n,
+                               int32_t* page_table, const int32_t* dst_slots, void* stream_v, bool two_streams,
+                               void* stream2_v) {
     if (int rc = check_layer(c, layer, true)) return rc;
     LayerMeta& L = c->layers[layer];
     if (!c->arenas_bound || !L.bound) return set_error(FLUXMOE_ESTATE, "arenas or layer %u not bound", layer);
@@ -900,14 +909,35 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
             HIPCHECK(launch_apply_updates(page_table, dcmd + upd_off, uint32_t(touched.size()), stream));
     } else {
     const uint64_t per_wg = uint64_t(waves_per_wg) * c->tune_blocks_per_wave;
-    uint32_t n_wg = uint32_t(std::min<uint64_t>((total + per_wg - 1) / per_wg, 1u << 20));
-    n_wg = std::max(n_wg, 2u);
-    uint32_t split = uint32_t((uint64_t(n_wg) * cmd->total_blocks[1] + total / 2) / total);
-    split = std::min(std::max(split, 1u), n_wg - 1);
-    args.wg_split = split;
-    HIPCHECK(span_begin(c, 0, stream));
-    HIPCHECK(launch_decode(args, n_wg, waves_per_wg, stream));
-    HIPCHECK(span_end(c, stream));
+    auto wgs_for = [&](uint64_t blocks) { return uint32_t(std::min<uint64_t>((blocks + per_wg - 1) / per_wg, 1u << 20)); };
+    if (two_streams && cmd->total_blocks[0] && cmd->total_blocks[1]) {
+        // one launch per tensor type: the type-2 list on the second stream (after everything this call has
+        // enqueued on the first one so far), the type-1 list and the page-table updates on the first
+        hipStream_t stream2 = static_cast<hipStream_t>(stream2_v);
+        HIPCHECK(hipEventRecord(c->ev_fork, stream));
+        HIPCHECK(hipStreamWaitEvent(stream2, c->ev_fork, 0));
+        DecodeArgs a2 = args;
+        const uint32_t n2 = wgs_for(cmd->total_blocks[1]);
+        a2.wg_split = n2;                       // every workgroup serves the type-2 list
+        a2.apply_updates = 0;
+        HIPCHECK(launch_decode(a2, n2, waves_per_wg, stream2));
+        HIPCHECK(hipEventRecord(c->ev_join, stream2));
+        args.wg_split = 0;                      // every workgroup serves the type-1 list
+        args.apply_updates = 1;
+        HIPCHECK(span_begin(c, 0, stream));
+        HIPCHECK(launch_decode(args, wgs_for(cmd->total_blocks[0]), waves_per_wg, stream));
+        HIPCHECK(span_end(c, stream));
+        HIPCHECK(hipStreamWaitEvent(stream, c->ev_join, 0));
+    } else {
+        uint32_t n_wg = std::max(wgs_for(total), 2u);
+        uint32_t split = uint32_t((uint64_t(n_wg) * cmd->total_blocks[1] + total / 2) / total);
+        split = std::min(std::max(split, 1u), n_wg - 1);
+        args.wg_split = split;
+        args.apply_updates = 1;
+        HIPCHECK(span_begin(c, 0, stream));
+        HIPCHECK(launch_decode(args, n_wg, waves_per_wg, stream));
+        HIPCHECK(span_end(c, stream));
+    }
     }
     HIPCHECK(hipEventRecord(c->ring_ev[slot], stream));
     c->ring_used[slot] = true;
@@ -919,6 +949,17 @@ int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_id
     HIPCHECK(hipEventRecord(c->ev_load[layer], stream));
     c->load_valid[layer] = 1;
     return FLUXMOE_OK;
+}
+
+int fluxmoe_materialize(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, uint32_t n,
+                        int32_t* page_table, const int32_t* dst_slots, void* stream) {
+    return materialize_enqueue(c, layer, expert_ids, n, page_table, dst_slots, stream, false, nullptr);
+}
+
+int fluxmoe_materialize_two_streams(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, uint32_t n,
+                                    int32_t* page_table, const int32_t* dst_slots, void* stream,
+                                    void* stream_type2) {
+    return materialize_enqueue(c, layer, expert_ids, n, page_table, dst_slots, stream, stream_type2 != stream, stream_type2);
 }
 
 int fluxmoe_release(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, uint32_t n,

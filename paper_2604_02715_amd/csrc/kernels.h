@@ -54,7 +54,7 @@ struct DecodeArgs {
     uint32_t jobs_offset[2];     // byte offsets of the two job lists from cmd
     uint32_t upd_offset;         // byte offset of the int2 (index, value) page-table updates
     uint32_t wg_split;           // workgroups [0, wg_split) decode type 2, the rest type 1
-    uint32_t reserved;
+    uint32_t apply_updates;      // non-zero: workgroup 0 applies the page-table updates
     const uint32_t* lut[2];      // device decode tables, [0] type 1, [1] type 2
     int32_t* page_table;         // device
     uint32_t* error_word;        // device

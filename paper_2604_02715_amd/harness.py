@@ -153,6 +153,10 @@ class ExpertPool:
         B.fluxmoe_materialize(self.ctx, layer, expert_ids, self.page_table.data_ptr(), dst_slots,
                               _sptr(stream))
 
+    def materialize_two_streams(self, layer, expert_ids, dst_slots, stream, stream_type2):
+        B.fluxmoe_materialize_two_streams(self.ctx, layer, expert_ids, self.page_table.data_ptr(), dst_slots,
+                                          _sptr(stream), _sptr(stream_type2))
+
     def release(self, layer, expert_ids=None, stream=None):
         B.fluxmoe_release(self.ctx, layer, expert_ids, self.page_table.data_ptr(), _sptr(stream))
 
