@@ -483,13 +483,12 @@ __global__ __launch_bounds__(256) void gemm1_swiglu_kernel(FfnArgs a) {
 
 // y[split][row][n] = h[row][k range] W2[k range][n]
 template <int MI>
-__device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t, uint16_t* abuf) {
+__device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t, uint16_t* abuf, uint32_t col_wg, uint32_t split) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
-    const uint32_t strip = blockIdx.x * 4 + wave;
+    const uint32_t strip = col_wg * 4 + wave;
     const uint32_t n0 = strip * kStrip + 8u * (lane & 15);
     const bool col_ok = n0 < a.H;                 // wavefronts past the last strip still run (barriers below)
-    const uint32_t split = blockIdx.z;
     const uint32_t k_per = ((a.F + a.ksplit - 1) / a.ksplit + kChunk - 1) / kChunk * kChunk;
     const uint32_t k_begin = min(a.F, split * k_per);
     const uint32_t k_end = min(a.F, k_begin + k_per);
@@ -536,13 +535,22 @@ __device__ __forceinline__ void gemm2_body(const FfnArgs& a, const TileInfo& t, 
 template <int MI>
 __global__ __launch_bounds__(256) void gemm2_kernel(FfnArgs a) {
     __shared__ __align__(16) uint16_t abuf[2 * StripGemm<MI>::kABufElems];
+    // One-dimensional grid.  Workgroups go to the 8 XCDs round robin, so workgroup L runs on XCD L % 8; the
+    // column workgroups of one (tile, K split) all read the same rows of h, so they are numbered to land on
+    // one XCD back to back and find those rows in its L2 (on 8 XCDs each would fetch them from HBM again).
+    const uint32_t n_cw = (a.H + 4 * kStrip - 1) / (4 * kStrip);
+    const uint32_t xcd = blockIdx.x % 8u, q = blockIdx.x / 8u;
+    const uint32_t col_wg = q % n_cw;
+    const uint32_t pair = (q / n_cw) * 8u + xcd;             // (tile, split), tile-major
+    if (pair >= a.tiles_cap * a.ksplit) return;
+    const uint32_t tile = pair / a.ksplit, split = pair % a.ksplit;
     TileInfo t;
-    if (!tile_info(a, blockIdx.y, t)) return;
-    if (MI > 1 && t.rows <= 16) gemm2_body<1>(a, t, abuf);
-    else if (MI > 2 && t.rows <= 32) gemm2_body<2>(a, t, abuf);
-    else if (MI > 4 && t.rows <= 64) gemm2_body<4>(a, t, abuf);
-    else if (MI > 6 && t.rows <= 96) gemm2_body<6>(a, t, abuf);
-    else gemm2_body<MI>(a, t, abuf);
+    if (!tile_info(a, tile, t)) return;
+    if (MI > 1 && t.rows <= 16) gemm2_body<1>(a, t, abuf, col_wg, split);
+    else if (MI > 2 && t.rows <= 32) gemm2_body<2>(a, t, abuf, col_wg, split);
+    else if (MI > 4 && t.rows <= 64) gemm2_body<4>(a, t, abuf, col_wg, split);
+    else if (MI > 6 && t.rows <= 96) gemm2_body<6>(a, t, abuf, col_wg, split);
+    else gemm2_body<MI>(a, t, abuf, col_wg, split);
 }
 
 // ------------------------------------------------------------------ large row tiles (MFMA bound)
@@ -1336,7 +1344,7 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
     const uint32_t strips1 = (a.F + kStrip - 1) / kStrip;
     const uint32_t strips2 = (a.H + kStrip - 1) / kStrip;
     const dim3 g1((strips1 + 1) / 2, a.tiles_cap, 1);
-    const dim3 g2((strips2 + 3) / 4, a.tiles_cap, a.ksplit);
+    const dim3 g2(((a.tiles_cap * a.ksplit + 7) / 8 * 8) * ((strips2 + 3) / 4), 1, 1);
     if (a.m_tile == 256) {
         const size_t lds_bytes = 4 * size_t(kTM) * kLdsPitch * sizeof(uint16_t);
         const bool four = a.tiled_waves == 4;
