@@ -26,6 +26,9 @@
 // 23..30 second exponent, 31 = only the first symbol is valid.
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
+#include <cstring>
+
 #include "kernels.h"
 
 namespace fluxmoe {
@@ -178,7 +181,12 @@ __global__ __launch_bounds__(WAVES * 64) void decode_kernel(DecodeArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the command buffer: in device memory, or - when small - inside the kernel arguments, which are read in
+    // place through the kernel-argument segment's address (taking the address of `a`'s member would copy it)
     const DecodeCmd* cmd = a.cmd;
+    if (a.inline_cmd)
+        cmd = reinterpret_cast<const DecodeCmd*>(reinterpret_cast<const char*>((const void*)__builtin_amdgcn_kernarg_segment_ptr()) +
+                                                 offsetof(DecodeArgs, inline_words));
 
     // page-table updates ride along with the first workgroup
     if (blockIdx.x == 0 && a.apply_updates) {
@@ -267,6 +275,27 @@ __global__ void apply_updates_kernel(int32_t* page_table, const int2* upd, uint3
     if (i < n) page_table[upd[i].x] = upd[i].y;
 }
 }  // namespace
+
+namespace {
+__global__ void apply_updates_inline_kernel(InlineUpdates u) {
+    const int2* upd = reinterpret_cast<const int2*>(reinterpret_cast<const char*>((const void*)__builtin_amdgcn_kernarg_segment_ptr()) +
+                                                    offsetof(InlineUpdates, upd));
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < u.n) u.page_table[upd[i].x] = upd[i].y;
+}
+}  // namespace
+
+hipError_t launch_apply_updates_inline(int32_t* page_table, const int32_t* host_upd, uint32_t n, hipStream_t stream) {
+    if (n == 0) return hipSuccess;
+    if (n > kInlineUpdates) return hipErrorInvalidValue;
+    InlineUpdates u;
+    u.page_table = page_table;
+    u.n = n;
+    u.pad = 0;
+    std::memcpy(u.upd, host_upd, size_t(n) * 8);
+    hipLaunchKernelGGL(apply_updates_inline_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, u);
+    return hipGetLastError();
+}
 
 hipError_t launch_apply_updates(int32_t* page_table, const void* upd, uint32_t n, hipStream_t stream) {
     if (n == 0) return hipSuccess;

@@ -887,20 +887,39 @@ static int materialize_enqueue(fluxmoe_ctx* c, uint32_t layer, const int32_t* ex
     // a release of this layer issued on another stream writes the same page-table row
     if (c->rel_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_rel[layer], 0));
     if (wait_copy) HIPCHECK(hipStreamWaitEvent(stream, c->ev_copied[half], 0));
-    const size_t used = upd_off + touched.size() * 8;
-    HIPCHECK(hipMemcpyAsync(dcmd, hcmd, used, hipMemcpyHostToDevice, stream));
-    for (const DenseCopy& dc : dense_copies)
-        HIPCHECK(hipMemcpyAsync(dc.dst, dc.src, dc.bytes, hipMemcpyDeviceToDevice, stream));
 
     DecodeArgs args{};
-    args.cmd = reinterpret_cast<const DecodeCmd*>(dcmd);
-    args.jobs_offset[0] = jobs_off[0];
-    args.jobs_offset[1] = jobs_off[1];
-    args.upd_offset = upd_off;
     args.lut[0] = reinterpret_cast<const uint32_t*>(c->ws + c->lut_off + (uint64_t(layer) * 2 + 0) * kLutBytes);
     args.lut[1] = reinterpret_cast<const uint32_t*>(c->ws + c->lut_off + (uint64_t(layer) * 2 + 1) * kLutBytes);
     args.page_table = page_table;
     args.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
+    // A command that is small enough travels inside the kernel arguments, packed without the gaps of the
+    // ring slot's fixed layout; a larger one is uploaded into the ring slot in front of the kernel.
+    const uint64_t decode_blocks = uint64_t(cmd->total_blocks[0]) + cmd->total_blocks[1];
+    const size_t jobs_bytes[2] = {cmd->n_jobs[0] * sizeof(DecodeJob), cmd->n_jobs[1] * sizeof(DecodeJob)};
+    const size_t packed = sizeof(DecodeCmd) + jobs_bytes[0] + jobs_bytes[1] + touched.size() * 8;
+    if (decode_blocks > 0 && packed <= kInlineCmdBytes) {
+        uint8_t* w = reinterpret_cast<uint8_t*>(args.inline_words);
+        std::memcpy(w, cmd, sizeof(DecodeCmd));
+        args.jobs_offset[0] = uint32_t(sizeof(DecodeCmd));
+        args.jobs_offset[1] = uint32_t(args.jobs_offset[0] + jobs_bytes[0]);
+        args.upd_offset = uint32_t(args.jobs_offset[1] + jobs_bytes[1]);
+        std::memcpy(w + args.jobs_offset[0], hcmd + jobs_off[0], jobs_bytes[0]);
+        std::memcpy(w + args.jobs_offset[1], hcmd + jobs_off[1], jobs_bytes[1]);
+        std::memcpy(w + args.upd_offset, hcmd + upd_off, touched.size() * 8);
+        args.inline_cmd = 1;
+        args.cmd = nullptr;
+    } else {
+        const size_t used = upd_off + touched.size() * 8;
+        HIPCHECK(hipMemcpyAsync(dcmd, hcmd, used, hipMemcpyHostToDevice, stream));
+        args.cmd = reinterpret_cast<const DecodeCmd*>(dcmd);
+        args.jobs_offset[0] = jobs_off[0];
+        args.jobs_offset[1] = jobs_off[1];
+        args.upd_offset = upd_off;
+        args.inline_cmd = 0;
+    }
+    for (const DenseCopy& dc : dense_copies)
+        HIPCHECK(hipMemcpyAsync(dc.dst, dc.src, dc.bytes, hipMemcpyDeviceToDevice, stream));
     const int waves_per_wg = c->tune_waves;
     const uint64_t total = uint64_t(cmd->total_blocks[0]) + cmd->total_blocks[1];
     if (total == 0) {
@@ -995,8 +1014,12 @@ int fluxmoe_release(fluxmoe_ctx* c, uint32_t layer, const int32_t* expert_ids, u
     // the entries are read by the layer's FFN and written by its materialize, possibly on other streams
     if (c->infer_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_infer[layer], 0));
     if (c->load_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_load[layer], 0));
-    HIPCHECK(hipMemcpyAsync(dcmd, hcmd, size_t(m) * 8, hipMemcpyHostToDevice, stream));
-    HIPCHECK(launch_apply_updates(page_table, dcmd, m, stream));
+    if (m <= kInlineUpdates) {
+        HIPCHECK(launch_apply_updates_inline(page_table, upd, m, stream));     // the pairs travel in the kernel arguments
+    } else {
+        HIPCHECK(hipMemcpyAsync(dcmd, hcmd, size_t(m) * 8, hipMemcpyHostToDevice, stream));
+        HIPCHECK(launch_apply_updates(page_table, dcmd, m, stream));
+    }
     HIPCHECK(hipEventRecord(c->ev_rel[layer], stream));
     c->rel_valid[layer] = 1;
     HIPCHECK(hipEventRecord(c->ring_ev[slot], stream));

@@ -49,15 +49,31 @@ struct DecodeCmd {
 };
 static_assert(sizeof(DecodeCmd) == 32, "DecodeCmd layout");
 
+// A small command buffer travels inside the kernel arguments (no separate upload, which costs a copy
+// and a dependency in front of the kernel); kernel arguments are limited to 4 KiB in all.
+constexpr uint32_t kInlineCmdBytes = 3584;
+
 struct DecodeArgs {
-    const DecodeCmd* cmd;        // device
-    uint32_t jobs_offset[2];     // byte offsets of the two job lists from cmd
+    const DecodeCmd* cmd;        // device; ignored when inline_cmd is set
+    uint32_t jobs_offset[2];     // byte offsets of the two job lists from the command header
     uint32_t upd_offset;         // byte offset of the int2 (index, value) page-table updates
     uint32_t wg_split;           // workgroups [0, wg_split) decode type 2, the rest type 1
     uint32_t apply_updates;      // non-zero: workgroup 0 applies the page-table updates
+    uint32_t inline_cmd;         // non-zero: the command buffer is inline_words below
     const uint32_t* lut[2];      // device decode tables, [0] type 1, [1] type 2
     int32_t* page_table;         // device
     uint32_t* error_word;        // device
+    uint32_t inline_words[kInlineCmdBytes / 4];
+};
+static_assert(sizeof(DecodeArgs) <= 4096 - 256, "kernel arguments must stay under 4 KiB with room for the hidden ones");
+
+// Page-table updates small enough to travel inside the kernel arguments.
+constexpr uint32_t kInlineUpdates = 448;
+struct InlineUpdates {
+    int32_t* page_table;
+    uint32_t n;
+    uint32_t pad;
+    int32_t upd[2 * kInlineUpdates];   // (index, value) pairs
 };
 
 hipError_t launch_decode(const DecodeArgs& args, uint32_t n_workgroups, int waves_per_wg,
@@ -67,6 +83,8 @@ hipError_t launch_stream_copy(void* dst, const void* src, uint64_t bytes, uint32
                               hipStream_t stream);
 // page_table[upd[i].x] = upd[i].y for i < n (upd: device int2 list)
 hipError_t launch_apply_updates(int32_t* page_table, const void* upd, uint32_t n, hipStream_t stream);
+// the same with the (index, value) pairs read from host memory now and carried in the kernel arguments; n <= kInlineUpdates
+hipError_t launch_apply_updates_inline(int32_t* page_table, const int32_t* host_upd, uint32_t n, hipStream_t stream);
 
 // ---------------------------------------------------------------- expert FFN
 struct FfnArgs {
