@@ -927,7 +927,9 @@ static int materialize_enqueue(fluxmoe_ctx* c, uint32_t layer, const int32_t* ex
         if (!touched.empty())
             HIPCHECK(launch_apply_updates(page_table, dcmd + upd_off, uint32_t(touched.size()), stream));
     } else {
-    const uint64_t per_wg = uint64_t(waves_per_wg) * c->tune_blocks_per_wave;
+    // blocks per workgroup: a few per wavefront, fewer when that would leave CUs without work
+    const uint64_t fill = total / (3ull * uint64_t(std::max(c->n_cus, 1)));
+    const uint64_t per_wg = std::max<uint64_t>(waves_per_wg, std::min<uint64_t>(uint64_t(waves_per_wg) * c->tune_blocks_per_wave, fill));
     auto wgs_for = [&](uint64_t blocks) { return uint32_t(std::min<uint64_t>((blocks + per_wg - 1) / per_wg, 1u << 20)); };
     if (two_streams && cmd->total_blocks[0] && cmd->total_blocks[1]) {
         // one launch per tensor type: the type-2 list on the second stream (after everything this call has
