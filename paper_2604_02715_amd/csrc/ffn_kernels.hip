@@ -366,10 +366,12 @@ struct StripGemm {
     }
 };
 
-__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
-    uint32_t u = __float_as_uint(x);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return u >> 16;
+// Two FP32 values rounded to BF16 (nearest even) and packed, lo in bits 0..15: one v_cvt_pk_bf16_f32.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 struct TileInfo {
@@ -443,19 +445,18 @@ __device__ __forceinline__ void gemm1_swiglu_body(const FfnArgs& a, const TileIn
         for (int r = 0; r < 4; ++r) {
             const int32_t row = mi * 16 + 4 * (lane >> 4) + r;
             if (row >= t.rows) continue;
-            uint32_t hb[8];
+            float hv[8];
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
                 const float ga = g.acc[mi][c][r];
                 const float up = xch[pair * (MI * 32) + (mi * 8 + c) * 4 + r][lane];
-                const float h = swiglu(ga, up);
-                hb[c] = f32_to_bf16_rne(h);
+                hv[c] = swiglu(ga, up);
             }
             uint4 o;
-            o.x = hb[0] | (hb[1] << 16);
-            o.y = hb[2] | (hb[3] << 16);
-            o.z = hb[4] | (hb[5] << 16);
-            o.w = hb[6] | (hb[7] << 16);
+            o.x = pack_bf16_rne(hv[0], hv[1]);
+            o.y = pack_bf16_rne(hv[2], hv[3]);
+            o.z = pack_bf16_rne(hv[4], hv[5]);
+            o.w = pack_bf16_rne(hv[6], hv[7]);
             *reinterpret_cast<uint4*>(a.hbuf + size_t(t.row0 + row) * a.F + n0) = o;
         }
 }
@@ -764,14 +765,7 @@ __global__ __launch_bounds__(512) void gemm_tiled_kernel(FfnArgs a) {
             if (MODE == 1) {
                 const uint32_t col = n_base + 4u * q + 2u * wn;      // two adjacent columns
                 if (col >= N) continue;
-                uint32_t packed = 0;
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const float ga_ = acc[i][j][r];
-                    const float up = acc[i][j + 2][r];
-                    const float h = swiglu(ga_, up);
-                    packed |= f32_to_bf16_rne(h) << (16 * j);
-                }
+                const uint32_t packed = pack_bf16_rne(swiglu(acc[i][0][r], acc[i][2][r]), swiglu(acc[i][1][r], acc[i][3][r]));
                 *reinterpret_cast<uint32_t*>(a.hbuf + size_t(t.row0 + row) * a.F + col) = packed;
             } else {
 #pragma unroll
@@ -972,14 +966,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             if (MODE == 1) {
                 const uint32_t col = n_base + 4u * q + 2u * wn;
                 if (col >= N) continue;
-                uint32_t packed = 0;
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const float ga_ = acc[i][j][r];
-                    const float up = acc[i][j + 2][r];
-                    const float h = swiglu(ga_, up);
-                    packed |= f32_to_bf16_rne(h) << (16 * j);
-                }
+                const uint32_t packed = pack_bf16_rne(swiglu(acc[i][0][r], acc[i][2][r]), swiglu(acc[i][1][r], acc[i][3][r]));
                 *reinterpret_cast<uint32_t*>(a.hbuf + size_t(t.row0 + row) * a.F + col) = packed;
             } else {
 #pragma unroll
@@ -1232,6 +1219,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
         // a lane holds one h column; neighbouring lanes swap values (DPP) so that even lanes store
         // columns (q, q + 1) of an even row and odd lanes columns (q - 1, q) of the next row: 4-byte
         // stores instead of 2-byte ones
+        // v_perm_b32(other, own, sel): selector bytes 0..3 pick from own, 4..7 from other
+        const uint32_t pair_sel = (q & 1) ? 0x03020706u : 0x05040100u;
 #pragma unroll
         for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
@@ -1239,16 +1228,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
                 const int32_t row = wm * kWaveRows + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3) + (q & 1);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
-                    uint32_t hb[2];
-#pragma unroll
-                    for (int d = 0; d < 2; ++d) {
-                        const float ga_ = acc[i][j][r + d];
-                        const float up = acc[i][j + 2][r + d];
-                        hb[d] = f32_to_bf16_rne(swiglu(ga_, up));
-                    }
-                    const uint32_t p0 = uint32_t(__builtin_amdgcn_update_dpp(0, int(hb[0]), 0xB1, 0xF, 0xF, true));
-                    const uint32_t p1 = uint32_t(__builtin_amdgcn_update_dpp(0, int(hb[1]), 0xB1, 0xF, 0xF, true));
-                    const uint32_t packed = (q & 1) ? (p1 | (hb[1] << 16)) : (hb[0] | (p0 << 16));
+                    // own = (row r, row r + 1) of this lane's column; the neighbouring lane's pair comes by DPP
+                    // (quad_perm 1,0,3,2); an even lane keeps both lanes' row-r values, an odd lane both
+                    // lanes' row-(r + 1) values, lower column first: one byte permute with a per-lane selector
+                    const uint32_t own = pack_bf16_rne(swiglu(acc[i][j][r], acc[i][j + 2][r]),
+                                                       swiglu(acc[i][j][r + 1], acc[i][j + 2][r + 1]));
+                    const uint32_t other = uint32_t(__builtin_amdgcn_update_dpp(0, int(own), 0xB1, 0xF, 0xF, true));
+                    const uint32_t packed = __builtin_amdgcn_perm(other, own, pair_sel);
                     const uint32_t col = n_base + 64u * wn + 32u * j + (q & ~1);
                     if (row < t.rows && col < N)
                         *reinterpret_cast<uint32_t*>(a.hbuf + size_t(t.row0 + row) * a.F + col) = packed;
