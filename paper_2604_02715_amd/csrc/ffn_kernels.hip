@@ -24,6 +24,7 @@
 // the matrix cores.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "kernels.h"
@@ -992,6 +993,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 // eight wavefronts, wave tiles and sub-step schedule as gemm_tiled_kernel.
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+// Measurement aid, compile time only (python -m paper_2604_02715_amd.build -DFLUXMOE_D2L_PROBE=<bits>): parts of
+// gemm_d2l_kernel's k loop left out to see what each costs.  The results are wrong with any bit set; every
+// access that remains is one the full kernel makes too.  1: fragments are read from LDS once per tile only;
+// 2: no A loads after the prologue; 4: no B loads after the prologue; 8: no waits for loads inside the loop
+// (one wait after it); 16: every B load fetches the tile's first k block (stays cache resident).
+#ifndef FLUXMOE_D2L_PROBE
+#define FLUXMOE_D2L_PROBE 0
+#endif
 
 template <int MODE, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
@@ -1017,8 +1026,16 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     const uint32_t pair = (jj / (kSuperM * kSuperN)) * 8u + xcd;
     const uint32_t st = pair / n_split, split = pair % n_split;
     const uint32_t within = jj % (kSuperM * kSuperN);
-    const uint32_t row_tile = (st / n_sn) * kSuperM + within / kSuperN;
-    const uint32_t col_tile = (st % n_sn) * kSuperN + within % kSuperN;
+    // Super-tiles are taken in groups of tiled_group super-rows (the row tiles of about one expert): for
+    // each column block of the group, its super-rows run next to each other in time on different XCDs,
+    // so the expert's weights for that column block leave HBM once and the other XCDs find them in the
+    // memory-side cache, while the group's activations stay there across the column blocks.
+    // (The second product has two column blocks at most and measured no gain: it keeps super-row order.)
+    const uint32_t group = MODE == 1 ? a.tiled_group : 1u;
+    const uint32_t per_group = group * n_sn;
+    const uint32_t grp = st / per_group, in_grp = st % per_group;
+    const uint32_t row_tile = (grp * group + in_grp % group) * kSuperM + within / kSuperN;
+    const uint32_t col_tile = (in_grp / group) * kSuperN + within % kSuperN;
     if (row_tile >= n_rt || col_tile >= n_ct) return;
     TileInfo t;
     if (!tile_info(a, row_tile, t)) return;
@@ -1084,7 +1101,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
         dma16(a_base + size_t(k0) * 2 + a_off[n], lds_base + a_stage_off + (wave * kDma + n) * 1024);
     };
     auto dma_b = [&](uint32_t k0, int b_stage_off, int n) __attribute__((always_inline)) {
-        dma16(b_base + size_t(k0) * N * 2 + b_off[n], lds_base + 2 * kStageBytes + b_stage_off + (wave * kDma + n) * 1024);
+        dma16(b_base + size_t((FLUXMOE_D2L_PROBE & 16) ? 0u : k0) * N * 2 + b_off[n], lds_base + 2 * kStageBytes + b_stage_off + (wave * kDma + n) * 1024);
     };
 
     // ---- fragment addresses (bytes from the start of stage 0 of the operand's region)
@@ -1154,12 +1171,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
 #pragma unroll
             for (int n = 0; n < kMfma; ++n) {
                 if (ACT.value) mfma_item(set, n);
-                if (READ.value && ACT.value && n < kFrag) lfrag_item(other, next_ks, set ^ 1, n);
-                if (DMA_B.value && (n & 1)) dma_b(k0 + 2 * kTK, b_plus2, n >> 1);
-                if (DMA_A.value && (n & 1)) dma_a(k0 + 2 * kTK, a_own, n >> 1);
+                if (READ.value && ACT.value && n < kFrag && !(FLUXMOE_D2L_PROBE & 1)) lfrag_item(other, next_ks, set ^ 1, n);
+                if (DMA_B.value && (n & 1) && !(FLUXMOE_D2L_PROBE & 4)) dma_b(k0 + 2 * kTK, b_plus2, n >> 1);
+                if (DMA_A.value && (n & 1) && !(FLUXMOE_D2L_PROBE & 2)) dma_a(k0 + 2 * kTK, a_own, n >> 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (READ.value && ACT.value) {
+            if (READ.value && ACT.value && !(FLUXMOE_D2L_PROBE & 1)) {
 #pragma unroll
                 for (int n = kMfma; n < kFrag; ++n) lfrag_item(other, next_ks, set ^ 1, n);
             }
@@ -1170,8 +1187,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
         sub(0, 0, 1, T{}, LOAD_B, F{});                       // sub-step 0
         sub(1, 0, 2, T{}, F{}, F{});                          // sub-step 1
         sub(0, 0, 3, T{}, F{}, F{});                          // sub-step 2
-        if (LOAD_B.value) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kDma) : "memory");   // all but this step's own B loads have landed
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (!(FLUXMOE_D2L_PROBE & 8)) {
+            if (LOAD_B.value) asm volatile("s_waitcnt vmcnt(%0)" :: "n"(kDma) : "memory");   // all but this step's own B loads have landed
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
         __syncthreads();                                      // all reads of this step's stages are in registers
         sub(1, 1, 0, NEXT, F{}, LOAD_A);                      // sub-step 3
         // advance to the next step's stages
@@ -1204,6 +1223,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
         if (ACT.value) {
 #pragma unroll
             for (int n = 0; n < kFrag; ++n) lfrag_item(0, 0, 0, n);
+            if (FLUXMOE_D2L_PROBE & 1) {
+#pragma unroll
+                for (int n = 0; n < kFrag; ++n) lfrag_item(0, 1, 1, n);
+            }
         }
         uint32_t s = 0;
         for (; s + 2 < n_steps; ++s) step(s * kTK, Yes{}, Yes{}, Yes{}, ACT);
@@ -1211,6 +1234,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
         step(0, No{}, No{}, No{}, ACT);
     };
     if (wm * kWaveRows < t.rows) k_loop(Yes{}); else k_loop(No{});
+    if (FLUXMOE_D2L_PROBE & 8) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); }
 
     // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4;
     // fragment j of this wavefront holds tile columns 128 wn + 32 j + q (MODE 2) or, in MODE 1,
@@ -1319,9 +1343,15 @@ hipError_t launch_mfma_probe(const void* operands, float* out, uint32_t n_workgr
     return hipGetLastError();
 }
 
-hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook hook, void* user) {
+hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHook hook, void* user) {
     (void)n_cus;
-    if (a.T == 0) return hipSuccess;
+    if (args.T == 0) return hipSuccess;
+    FfnArgs a = args;
+    {   // super-rows (4 row tiles of 256) that an expert fills on average, between 1 and 8 (one per XCD)
+        const uint64_t pairs = uint64_t(a.T) * a.K;
+        const uint64_t avg = pairs / std::max<uint64_t>(1, std::min<uint64_t>(a.E, pairs));
+        a.tiled_group = uint32_t(std::min<uint64_t>(8, std::max<uint64_t>(1, args.tiled_group ? args.tiled_group : (avg + 512) / 1024)));
+    }
     auto mark = [&](int kind, int begin) { if (hook) hook(user, kind, begin, stream); };
     const size_t sh = (2 * size_t(a.E) + 1024) * sizeof(int32_t);
     mark(1, 1);
@@ -1368,7 +1398,8 @@ hipError_t launch_ffn(const FfnArgs& a, int n_cus, hipStream_t stream, SpanHook 
         }
         mark(2, 1);
         auto grid_for = [&](uint32_t n_ct, uint32_t n_split = 1) {
-            const uint32_t n_sm = (a.tiles_cap + kSuperM - 1) / kSuperM, n_sn = (n_ct + kSuperN - 1) / kSuperN;
+            const uint32_t n_sm = ((a.tiles_cap + kSuperM - 1) / kSuperM + a.tiled_group - 1) / a.tiled_group * a.tiled_group;
+            const uint32_t n_sn = (n_ct + kSuperN - 1) / kSuperN;
             const uint32_t supers = (n_sm * n_sn * n_split + 7) / 8 * 8;      // whole rounds over the 8 XCDs
             return dim3(supers * kSuperM * kSuperN, 1, 1);
         };

@@ -112,6 +112,7 @@ struct fluxmoe_ctx {
     int tune_blocks_per_wave = 3;
     int tune_tiled_waves = 2;             // FLUXMOE_FFN_TILED_WAVES: 2 = LDS-direct loads (default), 8 = register-staged,
                                           // 4 = register-staged with four wavefronts of 128 x 128
+    int tune_tiled_group = 0;             // FLUXMOE_FFN_TILED_GROUP: 1..8 super-rows per group of the tiled gate/up kernel, 0 = from the shape
     // optional kernel timing (fluxmoe_profile_*)
     bool profiling = false;
     uint32_t profile_mask = 0x1F;         // kinds that are bracketed while profiling
@@ -367,6 +368,10 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     if (const char* v = std::getenv("FLUXMOE_FFN_TILED_WAVES")) {
         const int w = std::atoi(v);
         if (w == 1 || w == 2 || w == 4 || w == 8) c->tune_tiled_waves = w;
+    }
+    if (const char* v = std::getenv("FLUXMOE_FFN_TILED_GROUP")) {
+        const int w = std::atoi(v);
+        if (w >= 1 && w <= 8) c->tune_tiled_group = w;
     }
     *out_ctx = c;
     g_err[0] = 0;
@@ -1071,6 +1076,7 @@ static int expert_ffn_enqueue(fluxmoe_ctx* c, uint32_t layer, const uint16_t* to
     a.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
     a.pairs_cap = p.pairs_cap; a.tiles_cap = p.tiles_cap; a.m_tile = p.m_tile; a.ksplit = p.ksplit;
     a.tiled_waves = c->tune_tiled_waves;
+    a.tiled_group = uint32_t(c->tune_tiled_group);
 
     if (c->load_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_load[layer], 0));
     if (c->rel_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_rel[layer], 0));
@@ -1157,6 +1163,7 @@ int fluxmoe_shared_expert_ffn(fluxmoe_ctx* c, const uint16_t* w13, const uint16_
     a.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
     a.pairs_cap = p.pairs_cap; a.tiles_cap = p.tiles_cap; a.m_tile = p.m_tile; a.ksplit = p.ksplit;
     a.tiled_waves = c->tune_tiled_waves;
+    a.tiled_group = uint32_t(c->tune_tiled_group);
     HIPCHECK(launch_ffn(a, c->n_cus, stream, c->profiling ? ffn_span_hook : nullptr, c));
     return FLUXMOE_OK;
 }

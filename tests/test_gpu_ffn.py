@@ -103,6 +103,21 @@ def test_variants_of_the_tiled_kernels(monkeypatch, kw):
         assert offn.rel_frobenius(other, default) < 1e-5, variant
 
 
+def test_tile_order_of_the_tiled_gate_up_kernel_does_not_change_results(monkeypatch):
+    """FLUXMOE_FFN_TILED_GROUP sets how many super-rows (4 row tiles of 256) of the LDS-tiled gate/up
+    kernel share a column block in time.  It only renumbers workgroups: 12 row tiles (3 super-rows, the
+    last group partial) by 18 column tiles (3 column blocks, the last partial) must come out bit for bit
+    the same for every group size."""
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], tokens=3000, top_k=1, n_experts=2, n_slots=2, hidden=128, ffn=2304)
+    monkeypatch.setenv("FLUXMOE_FFN_TILED_GROUP", "1")
+    base = run_ffn_case(cfg, seed=2)
+    for group in ("2", "3", "8"):
+        monkeypatch.setenv("FLUXMOE_FFN_TILED_GROUP", group)
+        assert np.array_equal(run_ffn_case(cfg, seed=2), base), group
+    monkeypatch.delenv("FLUXMOE_FFN_TILED_GROUP")
+    assert np.array_equal(run_ffn_case(cfg, seed=2), base)
+
+
 def test_wave_mode_accumulates_to_the_single_shot_result():
     cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_slots=3)
     from oracle import paging
