@@ -45,16 +45,65 @@ constexpr int kStrip = 128;        // output columns per wavefront
 constexpr int kChunk = 32;         // k per MFMA step
 
 // ------------------------------------------------------------------ routing / grouping
+// Row tiles are handed out by size class: the body a tile runs and the time it takes grow with its rows,
+// and a launch ends when its last workgroup does, so the tiles with the most rows are numbered (and
+// therefore started) first and the many small ones fill in behind them.
+constexpr int kTileClasses = 5;
+__device__ __forceinline__ int tile_class(int32_t rows) {
+    return rows > 96 ? 0 : (rows > 64 ? 1 : (rows > 32 ? 2 : (rows > 16 ? 3 : 4)));
+}
+
+// Exclusive prefix sums over the 1024 threads of a workgroup for N values per thread at once; total[i]
+// receives the sum of v[i] over all threads.  tot: N * 17 ints of LDS.  Contains barriers.
+template <int N>
+__device__ __forceinline__ void block_scan_excl(const int32_t (&v)[N], int32_t (&excl)[N], int32_t (&total)[N], int32_t* tot) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t x[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        x[i] = v[i];
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int32_t y = __shfl_up(x[i], d, 64);
+            if (lane >= d) x[i] += y;
+        }
+        if (lane == 63) tot[i * 17 + wave] = x[i];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+            const int32_t w = lane < 16 ? tot[i * 17 + lane] : 0;
+            int32_t xs = w;
+#pragma unroll
+            for (int d = 1; d < 16; d <<= 1) {
+                const int32_t y = __shfl_up(xs, d, 64);
+                if (lane >= d) xs += y;
+            }
+            if (lane < 16) tot[i * 17 + lane] = xs - w;
+            if (lane == 15) tot[i * 17 + 16] = xs;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        excl[i] = x[i] - v[i] + tot[i * 17 + wave];
+        total[i] = tot[i * 17 + 16];
+    }
+    __syncthreads();
+}
+
 __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
-    extern __shared__ int32_t sh[];          // count[E], cursor[E], scan scratch[1024]
+    extern __shared__ int32_t sh[];          // count[E], cursor[E], scan scratch
     int32_t* count = sh;
     int32_t* cursor = sh + a.E;
     int32_t* scratch = sh + 2 * a.E;
-    __shared__ int32_t carry, tile_carry;
+    __shared__ int32_t class_total[kTileClasses];
     const int tid = threadIdx.x;
     const uint32_t pairs = a.T * a.K;
+    const int32_t m = int32_t(a.m_tile);
     for (uint32_t e = tid; e < a.E; e += 1024) count[e] = 0;
-    if (tid == 0) { carry = 0; tile_carry = 0; }
+    if (tid < kTileClasses) class_total[tid] = 0;
     __syncthreads();
     for (uint32_t p = tid; p < pairs; p += 1024) {
         const int32_t e = a.topk_ids[p];
@@ -69,52 +118,54 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
         if (keep) atomicAdd(&count[e], 1);
     }
     __syncthreads();
-    // exclusive scans over experts (rows and tiles), 1024 experts per round
+    // tiles per class over all experts (integer sums: the order of the additions does not matter)
+    for (uint32_t e = tid; e < a.E; e += 1024) {
+        const int32_t c = count[e];
+        if (c >= m) atomicAdd(&class_total[tile_class(m)], c / m);
+        if (c % m) atomicAdd(&class_total[tile_class(c % m)], 1);
+    }
+    __syncthreads();
+    int32_t class_base[kTileClasses];        // first tile number of each class; advanced round by round
+    int32_t n_tiles = 0;
+#pragma unroll
+    for (int k = 0; k < kTileClasses; ++k) { class_base[k] = n_tiles; n_tiles += class_total[k]; }
+    int32_t row_base = 0;
+    // experts in rounds of 1024, one per thread: exclusive scans of its rows and of its tiles in each class
     for (uint32_t base = 0; base < a.E; base += 1024) {
         const uint32_t e = base + tid;
         const int32_t c = (e < a.E) ? count[e] : 0;
-        const int32_t t = (c + int32_t(a.m_tile) - 1) / int32_t(a.m_tile);
-        // rows
-        scratch[tid] = c;
-        __syncthreads();
-        for (int d = 1; d < 1024; d <<= 1) {
-            const int32_t v = (tid >= d) ? scratch[tid - d] : 0;
-            __syncthreads();
-            scratch[tid] += v;
-            __syncthreads();
-        }
-        const int32_t row_excl = scratch[tid] - c + carry;
-        const int32_t row_total = scratch[1023];
-        __syncthreads();
-        // tiles
-        scratch[tid] = t;
-        __syncthreads();
-        for (int d = 1; d < 1024; d <<= 1) {
-            const int32_t v = (tid >= d) ? scratch[tid - d] : 0;
-            __syncthreads();
-            scratch[tid] += v;
-            __syncthreads();
-        }
-        const int32_t tile_excl = scratch[tid] - t + tile_carry;
-        const int32_t tile_total = scratch[1023];
-        __syncthreads();
+        const int32_t full = c / m, rem = c % m;
+        const int k_full = tile_class(m), k_rem = tile_class(rem);
+        int32_t v[1 + kTileClasses], excl[1 + kTileClasses], total[1 + kTileClasses];
+        v[0] = c;
+#pragma unroll
+        for (int k = 0; k < kTileClasses; ++k) v[1 + k] = (k == k_full ? full : 0) + ((rem && k == k_rem) ? 1 : 0);
+        block_scan_excl(v, excl, total, scratch);
         if (e < a.E) {
+            const int32_t row_excl = row_base + excl[0];
             a.expert_offset[e] = row_excl;
             a.expert_count[e] = c;
             cursor[e] = row_excl;
-            for (int32_t i = 0; i < t; ++i) {
-                if (uint32_t(tile_excl + i) < a.tiles_cap) {
-                    a.tile_expert[tile_excl + i] = int32_t(e);
-                    a.tile_row0[tile_excl + i] = row_excl + i * int32_t(a.m_tile);
-                }
+            const int32_t slot = c ? a.page_table[e] : -1;
+            int32_t at_full = 0, at_rem = 0;
+#pragma unroll
+            for (int k = 0; k < kTileClasses; ++k) {
+                if (k == k_full) at_full = class_base[k] + excl[1 + k];
+                if (k == k_rem) at_rem = class_base[k] + excl[1 + k] + (k == k_full ? full : 0);
             }
+            for (int32_t i = 0; i < full; ++i)
+                if (uint32_t(at_full + i) < a.tiles_cap) a.tile_rec[at_full + i] = make_int4(int32_t(e), row_excl + i * m, m, slot);
+            if (rem && uint32_t(at_rem) < a.tiles_cap) a.tile_rec[at_rem] = make_int4(int32_t(e), row_excl + full * m, rem, slot);
         }
-        if (tid == 0) { carry += row_total; tile_carry += tile_total; }
-        __syncthreads();
+        row_base += total[0];
+#pragma unroll
+        for (int k = 0; k < kTileClasses; ++k) class_base[k] += total[1 + k];
     }
+    // the records past the last tile read as empty tiles
+    for (uint32_t i = uint32_t(min(n_tiles, int32_t(a.tiles_cap))) + tid; i < a.tiles_cap; i += 1024) a.tile_rec[i] = make_int4(0, 0, 0, -1);
     if (tid == 0) {
-        a.expert_offset[a.E] = carry;
-        a.n_tiles[0] = min(tile_carry, int32_t(a.tiles_cap));
+        a.expert_offset[a.E] = row_base;
+        a.n_tiles[0] = min(n_tiles, int32_t(a.tiles_cap));
     }
     __syncthreads();
     for (uint32_t p = tid; p < pairs; p += 1024) {
@@ -379,13 +430,11 @@ struct TileInfo {
     int32_t expert, row0, rows, slot;
 };
 
+// One 16-byte load: route_sort_kernel wrote (expert, first row, rows, slot) for every tile number below
+// tiles_cap, with rows = 0 past the last tile.
 __device__ __forceinline__ bool tile_info(const FfnArgs& a, uint32_t tile, TileInfo& t) {
-    if (int32_t(tile) >= a.n_tiles[0]) return false;
-    t.expert = a.tile_expert[tile];
-    t.row0 = a.tile_row0[tile];
-    const int32_t end = a.expert_offset[t.expert] + a.expert_count[t.expert];
-    t.rows = min(int32_t(a.m_tile), end - t.row0);
-    t.slot = a.page_table[t.expert];
+    const int4 r = a.tile_rec[tile];
+    t.expert = r.x; t.row0 = r.y; t.rows = r.z; t.slot = r.w;
     return t.rows > 0 && t.slot >= 0;
 }
 

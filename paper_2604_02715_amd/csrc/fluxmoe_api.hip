@@ -55,7 +55,7 @@ struct StageHalf {
 struct FfnPlan {
     uint32_t m_tile, ksplit, pairs_cap, tiles_cap;
     uint64_t bytes;
-    uint64_t off_count, off_offset, off_sorted, off_pos, off_tile_e, off_tile_r, off_ntiles, off_h, off_y;
+    uint64_t off_count, off_offset, off_sorted, off_pos, off_tile, off_ntiles, off_h, off_y;
 };
 
 inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
@@ -204,8 +204,7 @@ FfnPlan plan_ffn(const FfnShape& c, uint32_t T, uint32_t K) {
     p.off_offset = take((E + 2) * 4);
     p.off_sorted = take(uint64_t(p.pairs_cap) * 4);
     p.off_pos = take(uint64_t(p.pairs_cap) * 4);
-    p.off_tile_e = take(uint64_t(p.tiles_cap) * 4);
-    p.off_tile_r = take(uint64_t(p.tiles_cap) * 4);
+    p.off_tile = take(uint64_t(p.tiles_cap) * 16);
     p.off_ntiles = take(4);
     p.off_h = take(uint64_t(p.pairs_cap) * F * 2);
     p.off_y = take(uint64_t(p.ksplit) * p.pairs_cap * H * 4);
@@ -1068,8 +1067,7 @@ static int expert_ffn_enqueue(fluxmoe_ctx* c, uint32_t layer, const uint16_t* to
     a.expert_offset = reinterpret_cast<int32_t*>(w + p.off_offset);
     a.sorted_pair = reinterpret_cast<int32_t*>(w + p.off_sorted);
     a.pair_pos = reinterpret_cast<int32_t*>(w + p.off_pos);
-    a.tile_expert = reinterpret_cast<int32_t*>(w + p.off_tile_e);
-    a.tile_row0 = reinterpret_cast<int32_t*>(w + p.off_tile_r);
+    a.tile_rec = reinterpret_cast<int4*>(w + p.off_tile);
     a.n_tiles = reinterpret_cast<int32_t*>(w + p.off_ntiles);
     a.hbuf = reinterpret_cast<uint16_t*>(w + p.off_h);
     a.ybuf = reinterpret_cast<float*>(w + p.off_y);
@@ -1155,8 +1153,7 @@ int fluxmoe_shared_expert_ffn(fluxmoe_ctx* c, const uint16_t* w13, const uint16_
     a.expert_offset = reinterpret_cast<int32_t*>(w + p.off_offset);
     a.sorted_pair = reinterpret_cast<int32_t*>(w + p.off_sorted);
     a.pair_pos = reinterpret_cast<int32_t*>(w + p.off_pos);
-    a.tile_expert = reinterpret_cast<int32_t*>(w + p.off_tile_e);
-    a.tile_row0 = reinterpret_cast<int32_t*>(w + p.off_tile_r);
+    a.tile_rec = reinterpret_cast<int4*>(w + p.off_tile);
     a.n_tiles = reinterpret_cast<int32_t*>(w + p.off_ntiles);
     a.hbuf = reinterpret_cast<uint16_t*>(w + p.off_h);
     a.ybuf = reinterpret_cast<float*>(w + p.off_y);

@@ -102,8 +102,7 @@ struct FfnArgs {
     int32_t* expert_offset;      // [E + 2]
     int32_t* sorted_pair;        // [pairs_cap]  pair index (t * K + k), grouped by expert
     int32_t* pair_pos;           // [pairs_cap]  position of a pair in sorted order, -1 = skipped
-    int32_t* tile_expert;        // [tiles_cap]
-    int32_t* tile_row0;          // [tiles_cap]  first sorted row of the tile
+    int4* tile_rec;              // [tiles_cap]  (expert, first sorted row, rows, slot); rows = 0 past the last tile
     int32_t* n_tiles;            // [1]
     uint16_t* hbuf;              // BF16 [pairs_cap][F]
     float* ybuf;                 // FP32 [ksplit][pairs_cap][H]
