@@ -105,17 +105,31 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
     for (uint32_t e = tid; e < a.E; e += 1024) count[e] = 0;
     if (tid < kTileClasses) class_total[tid] = 0;
     __syncthreads();
-    for (uint32_t p = tid; p < pairs; p += 1024) {
+    // a thread's first kKept pairs stay in registers for the scatter at the end (expert, or -1 for a pair
+    // that is skipped); batches with more pairs per thread read the rest again
+    constexpr int kKept = 8;
+    int32_t kept[kKept];
+    auto classify = [&](uint32_t p, bool report) {
         const int32_t e = a.topk_ids[p];
-        bool keep = false;
         if (e < 0 || uint32_t(e) >= a.E) {
-            atomicOr(a.error_word, 2u);
-        } else if (a.page_table[e] < 0) {
-            if (!(a.flags & 2u)) atomicOr(a.error_word, 2u);
-        } else {
-            keep = true;
+            if (report) atomicOr(a.error_word, 2u);
+            return -1;
         }
-        if (keep) atomicAdd(&count[e], 1);
+        if (a.page_table[e] < 0) {
+            if (report && !(a.flags & 2u)) atomicOr(a.error_word, 2u);
+            return -1;
+        }
+        return e;
+    };
+#pragma unroll
+    for (int i = 0; i < kKept; ++i) {
+        const uint32_t p = tid + 1024u * i;
+        kept[i] = p < pairs ? classify(p, true) : -1;
+        if (kept[i] >= 0) atomicAdd(&count[kept[i]], 1);
+    }
+    for (uint32_t p = tid + 1024u * kKept; p < pairs; p += 1024) {
+        const int32_t e = classify(p, true);
+        if (e >= 0) atomicAdd(&count[e], 1);
     }
     __syncthreads();
     // tiles per class over all experts (integer sums: the order of the additions does not matter)
@@ -168,15 +182,20 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
         a.n_tiles[0] = min(n_tiles, int32_t(a.tiles_cap));
     }
     __syncthreads();
-    for (uint32_t p = tid; p < pairs; p += 1024) {
-        const int32_t e = a.topk_ids[p];
+    auto place = [&](uint32_t p, int32_t e) {
         int32_t pos = -1;
-        if (e >= 0 && uint32_t(e) < a.E && a.page_table[e] >= 0) {
+        if (e >= 0) {
             pos = atomicAdd(&cursor[e], 1);
             a.sorted_pair[pos] = int32_t(p);
         }
         a.pair_pos[p] = pos;
+    };
+#pragma unroll
+    for (int i = 0; i < kKept; ++i) {
+        const uint32_t p = tid + 1024u * i;
+        if (p < pairs) place(p, kept[i]);
     }
+    for (uint32_t p = tid + 1024u * kKept; p < pairs; p += 1024) place(p, classify(p, false));
 }
 
 // SiLU(g) * u (Sec. 2.1's gated FFN) in FP32 with the hardware's exp2 and reciprocal, each within one

@@ -80,6 +80,8 @@ def test_c1_tiny():
     dict(tokens=300, top_k=1, n_experts=2, n_slots=2, hidden=256, ffn=1600),  # LDS-tiled path, K of the second product
                                                                               # split three ways (8, 8, 9 steps)
     dict(tokens=300, top_k=1, n_experts=2, n_slots=2, hidden=320, ffn=4096),  # split eight ways, ragged column tile
+    dict(tokens=4400, top_k=2, n_experts=64, n_slots=64, hidden=64, ffn=128),  # 8800 pairs: more than the grouping kernel
+                                                                               # keeps in registers between its passes
 ])
 def test_shapes(kw):
     run_ffn_case(inputs.scaled(inputs.CONFIGS["c1_tiny"], **kw), seed=1)
