@@ -14,13 +14,15 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-3
 
 
-def run_ffn_case(cfg, seed=0, waves=None, slot_perm=True):
+def run_ffn_case(cfg, seed=0, waves=None, slot_perm=True, ids_override=None):
     from gpu_common import build_pool
     pool, dense = build_pool(cfg, seed=seed)
     try:
         w13, w2 = dense[0]
         x = inputs.activations(cfg, 0, seed=seed)
         ids, g = inputs.routing(cfg, 0, seed=seed)
+        if ids_override is not None:
+            ids = ids_override(ids)
         union = inputs.routed_union(ids)
         xd = x.cuda()
         idd = torch.from_numpy(ids).cuda()
@@ -103,6 +105,26 @@ def test_variants_of_the_tiled_kernels(monkeypatch, kw):
         monkeypatch.setenv("FLUXMOE_FFN_TILED_WAVES", variant)
         other = run_ffn_case(cfg, seed=1)
         assert offn.rel_frobenius(other, default) < 1e-5, variant
+
+
+def test_more_experts_than_one_round_of_the_grouping_scans():
+    """The grouping kernel scans the experts 1024 at a time and carries row and tile offsets from round to
+    round: 1500 experts take two rounds."""
+    run_ffn_case(inputs.scaled(inputs.CONFIGS["c1_tiny"], tokens=300, top_k=4, n_experts=1500, n_slots=1500,
+                               hidden=64, ffn=128, routing="uniform"), seed=3)
+
+
+def test_all_pairs_on_one_expert_and_tiles_of_every_size_class():
+    """Degenerate routings of the tile list: every token on expert 3 (two full 128-row tiles and a 44-row
+    one with the strip kernels' largest tile forced), and expert row counts 1, 17, 33, 65, 97, 128, 129 that
+    put a tile into every size class of the grouping kernel at once."""
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], tokens=300, top_k=1, n_experts=8, n_slots=8, hidden=136, ffn=264)
+    run_ffn_case(cfg, seed=4, ids_override=lambda ids: np.full_like(ids, 3))
+    counts = [1, 17, 33, 65, 97, 128, 129]
+    cfg = inputs.scaled(cfg, tokens=sum(counts))
+    def spread(ids):
+        return np.repeat(np.arange(len(counts), dtype=ids.dtype), counts).reshape(ids.shape)
+    run_ffn_case(cfg, seed=5, ids_override=spread)
 
 
 def test_tile_order_of_the_tiled_gate_up_kernel_does_not_change_results(monkeypatch):
