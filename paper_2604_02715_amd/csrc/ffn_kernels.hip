@@ -95,28 +95,34 @@ __device__ __forceinline__ void block_scan_excl(const int32_t (&v)[N], int32_t (
 }
 
 __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
-    extern __shared__ int32_t sh[];          // count[E], cursor[E], scan scratch
+    extern __shared__ int32_t sh[];          // count[E], cursor[E], slot[E], scan scratch
     int32_t* count = sh;
     int32_t* cursor = sh + a.E;
-    int32_t* scratch = sh + 2 * a.E;
+    int32_t* slot_of = sh + 2 * a.E;         // this layer's page-table row: every later look-up is an LDS read
+    int32_t* scratch = sh + 3 * a.E;
     __shared__ int32_t class_total[kTileClasses];
     const int tid = threadIdx.x;
     const uint32_t pairs = a.T * a.K;
     const int32_t m = int32_t(a.m_tile);
-    for (uint32_t e = tid; e < a.E; e += 1024) count[e] = 0;
+    for (uint32_t e = tid; e < a.E; e += 1024) { count[e] = 0; slot_of[e] = a.page_table[e]; }
     if (tid < kTileClasses) class_total[tid] = 0;
+    // the first pairs' expert ids are fetched while the page-table row is on its way
+    constexpr int kKept = 8;
+    int32_t kept[kKept];
+#pragma unroll
+    for (int i = 0; i < kKept; ++i) {
+        const uint32_t p = tid + 1024u * i;
+        kept[i] = p < pairs ? a.topk_ids[p] : -1;
+    }
     __syncthreads();
     // a thread's first kKept pairs stay in registers for the scatter at the end (expert, or -1 for a pair
     // that is skipped); batches with more pairs per thread read the rest again
-    constexpr int kKept = 8;
-    int32_t kept[kKept];
-    auto classify = [&](uint32_t p, bool report) {
-        const int32_t e = a.topk_ids[p];
+    auto classify = [&](int32_t e, bool report) {
         if (e < 0 || uint32_t(e) >= a.E) {
             if (report) atomicOr(a.error_word, 2u);
             return -1;
         }
-        if (a.page_table[e] < 0) {
+        if (slot_of[e] < 0) {
             if (report && !(a.flags & 2u)) atomicOr(a.error_word, 2u);
             return -1;
         }
@@ -125,21 +131,26 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
 #pragma unroll
     for (int i = 0; i < kKept; ++i) {
         const uint32_t p = tid + 1024u * i;
-        kept[i] = p < pairs ? classify(p, true) : -1;
+        kept[i] = p < pairs ? classify(kept[i], true) : -1;
         if (kept[i] >= 0) atomicAdd(&count[kept[i]], 1);
     }
     for (uint32_t p = tid + 1024u * kKept; p < pairs; p += 1024) {
-        const int32_t e = classify(p, true);
+        const int32_t e = classify(a.topk_ids[p], true);
         if (e >= 0) atomicAdd(&count[e], 1);
     }
     __syncthreads();
-    // tiles per class over all experts (integer sums: the order of the additions does not matter)
-    for (uint32_t e = tid; e < a.E; e += 1024) {
-        const int32_t c = count[e];
-        if (c >= m) atomicAdd(&class_total[tile_class(m)], c / m);
-        if (c % m) atomicAdd(&class_total[tile_class(c % m)], 1);
+    // Tiles per class over all experts, needed before the first round's tiles can be numbered.  With one
+    // round (at most 1024 experts) the round's own scan delivers them; otherwise they are summed here
+    // (integer sums: the order of the additions does not matter).
+    const bool one_round = a.E <= 1024;
+    if (!one_round) {
+        for (uint32_t e = tid; e < a.E; e += 1024) {
+            const int32_t c = count[e];
+            if (c >= m) atomicAdd(&class_total[tile_class(m)], c / m);
+            if (c % m) atomicAdd(&class_total[tile_class(c % m)], 1);
+        }
+        __syncthreads();
     }
-    __syncthreads();
     int32_t class_base[kTileClasses];        // first tile number of each class; advanced round by round
     int32_t n_tiles = 0;
 #pragma unroll
@@ -156,12 +167,17 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
 #pragma unroll
         for (int k = 0; k < kTileClasses; ++k) v[1 + k] = (k == k_full ? full : 0) + ((rem && k == k_rem) ? 1 : 0);
         block_scan_excl(v, excl, total, scratch);
+        if (one_round) {
+            n_tiles = 0;
+#pragma unroll
+            for (int k = 0; k < kTileClasses; ++k) { class_base[k] = n_tiles; n_tiles += total[1 + k]; }
+        }
         if (e < a.E) {
             const int32_t row_excl = row_base + excl[0];
             a.expert_offset[e] = row_excl;
             a.expert_count[e] = c;
             cursor[e] = row_excl;
-            const int32_t slot = c ? a.page_table[e] : -1;
+            const int32_t slot = c ? slot_of[e] : -1;
             int32_t at_full = 0, at_rem = 0;
 #pragma unroll
             for (int k = 0; k < kTileClasses; ++k) {
@@ -196,7 +212,7 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
         const uint32_t p = tid + 1024u * i;
         if (p < pairs) place(p, kept[i]);
     }
-    for (uint32_t p = tid + 1024u * kKept; p < pairs; p += 1024) place(p, classify(p, false));
+    for (uint32_t p = tid + 1024u * kKept; p < pairs; p += 1024) place(p, classify(a.topk_ids[p], false));
 }
 
 // SiLU(g) * u (Sec. 2.1's gated FFN) in FP32 with the hardware's exp2 and reciprocal, each within one
@@ -1361,17 +1377,36 @@ __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     float* o = a.out + size_t(tok) * a.H + h;
     if (a.flags & 1u) s = *reinterpret_cast<const float4*>(o);
-    for (uint32_t k = 0; k < a.K; ++k) {
-        const int32_t pos = a.pair_pos[tok * a.K + k];
-        if (pos < 0) continue;
-        const float gate = a.topk_w[tok * a.K + k];
-        float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (uint32_t sp = 0; sp < a.ksplit; ++sp) {
-            const float4 v = *reinterpret_cast<const float4*>(
-                a.ybuf + (size_t(sp) * a.pairs_cap + pos) * a.H + h);
-            y.x += v.x; y.y += v.y; y.z += v.z; y.w += v.w;
+    // Eight pairs of the token at a time: their positions and gates are fetched together, then their rows of
+    // y, so that the loads overlap instead of following each other pair by pair.  A skipped pair reads row 0
+    // (a cache hit) and adds nothing; the sums run over the splits and then over k, in that order.
+    constexpr uint32_t kGroup = 8;
+    for (uint32_t k0 = 0; k0 < a.K; k0 += kGroup) {
+        int32_t pos[kGroup];
+        float gate[kGroup];
+#pragma unroll
+        for (uint32_t j = 0; j < kGroup; ++j) {
+            const bool in = k0 + j < a.K;
+            pos[j] = in ? a.pair_pos[tok * a.K + k0 + j] : -1;
+            gate[j] = in ? a.topk_w[tok * a.K + k0 + j] : 0.f;
         }
-        s.x += gate * y.x; s.y += gate * y.y; s.z += gate * y.z; s.w += gate * y.w;
+        float4 y[kGroup];
+#pragma unroll
+        for (uint32_t j = 0; j < kGroup; ++j) y[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (uint32_t sp = 0; sp < a.ksplit; ++sp) {
+            float4 v[kGroup];
+#pragma unroll
+            for (uint32_t j = 0; j < kGroup; ++j)
+                v[j] = *reinterpret_cast<const float4*>(a.ybuf + (size_t(sp) * a.pairs_cap + uint32_t(max(pos[j], 0))) * a.H + h);
+#pragma unroll
+            for (uint32_t j = 0; j < kGroup; ++j) {
+                if (pos[j] >= 0) { y[j].x += v[j].x; y[j].y += v[j].y; y[j].z += v[j].z; y[j].w += v[j].w; }
+            }
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < kGroup; ++j) {
+            if (pos[j] >= 0) { s.x += gate[j] * y[j].x; s.y += gate[j] * y[j].y; s.z += gate[j] * y[j].z; s.w += gate[j] * y[j].w; }
+        }
     }
     *reinterpret_cast<float4*>(o) = s;
 }
@@ -1425,7 +1460,7 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
         a.tiled_group = uint32_t(std::min<uint64_t>(8, std::max<uint64_t>(1, args.tiled_group ? args.tiled_group : (avg + 512) / 1024)));
     }
     auto mark = [&](int kind, int begin) { if (hook) hook(user, kind, begin, stream); };
-    const size_t sh = (2 * size_t(a.E) + 1024) * sizeof(int32_t);
+    const size_t sh = (3 * size_t(a.E) + 1024) * sizeof(int32_t);
     mark(1, 1);
     hipLaunchKernelGGL(route_sort_kernel, dim3(1), dim3(1024), sh, stream, a);
     mark(1, 0);
