@@ -6,7 +6,8 @@
 // expert sees few tokens and the FFN is bound by streaming the expert's weights once:
 //
 //   route_sort   one workgroup: counting sort of the (token, k) pairs by expert, skipping
-//                pairs whose expert has no slot; emits row tiles (expert, first row)
+//                pairs whose expert has no slot; emits one record per row tile (expert, first
+//                row, rows, slot), tiles with the most rows first
 //   gemm1        per (row tile, 128-column strip): a = X W1 and b = X W3 on two wavefronts
 //                with v_mfma_f32_16x16x32_bf16, h = silu(a) * b rounded to BF16
 //   gemm2        per (row tile, 128-column strip, K split): y = h W2, FP32 partial sums
