@@ -1091,7 +1091,9 @@ typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
 #define FLUXMOE_D2L_PROBE 0
 #endif
 
-template <int MODE, int WAVES>
+// WALK: a workgroup takes several tiles one after the other (see the tile loop at the end); without it the
+// launch has one workgroup per tile number and the code for the upcoming tile falls away.
+template <int MODE, int WAVES, bool WALK>
 __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     // WAVES = 8: wavefronts 4 (rows) x 2 (columns), 64 x 128 each, two per SIMD.  WAVES = 4: 2 x 2,
     // 128 x 128 each (256 accumulator registers), one per SIMD: a third less LDS read traffic per MFMA.
@@ -1111,10 +1113,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     // Workgroups go to the 8 XCDs round robin, so (super-tile, K split) pair number p runs on XCD
     // p % 8: the splits of one super-tile land on different XCDs
     const uint32_t n_split = MODE == 2 ? a.ksplit : 1u;
-    const uint32_t xcd = blockIdx.x % 8u, jj = blockIdx.x / 8u;
-    const uint32_t pair = (jj / (kSuperM * kSuperN)) * 8u + xcd;
-    const uint32_t st = pair / n_split, split = pair % n_split;
-    const uint32_t within = jj % (kSuperM * kSuperN);
     // Super-tiles are taken in groups of tiled_group super-rows (the row tiles of about one expert): for
     // each column block of the group, its super-rows run next to each other in time on different XCDs,
     // so the expert's weights for that column block leave HBM once and the other XCDs find them in the
@@ -1122,61 +1120,126 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     // (The second product has two column blocks at most and measured no gain: it keeps super-row order.)
     const uint32_t group = MODE == 1 ? a.tiled_group : 1u;
     const uint32_t per_group = group * n_sn;
-    const uint32_t grp = st / per_group, in_grp = st % per_group;
-    const uint32_t row_tile = (grp * group + in_grp % group) * kSuperM + within / kSuperN;
-    const uint32_t col_tile = (in_grp / group) * kSuperN + within % kSuperN;
-    if (row_tile >= n_rt || col_tile >= n_ct) return;
-    TileInfo t;
-    if (!tile_info(a, row_tile, t)) return;
-    const uint32_t n_base = col_tile * ncols_tile;
+    // Tile number L -> (row tile, column tile, K split); false when the number names no tile.  A workgroup
+    // takes the numbers blockIdx.x, blockIdx.x + gridDim.x, ...; gridDim.x is a multiple of 256 (or covers
+    // all numbers), so all of them lie on the XCD that runs this workgroup and at the same place of
+    // successive super-tiles.
+    const uint32_t total = a.tiled_total;
+    auto locate_unchecked = [&](uint32_t L, uint32_t& row_tile, uint32_t& col_tile, uint32_t& split) __attribute__((always_inline)) {
+        const uint32_t xcd = L % 8u, jj = L / 8u;
+        const uint32_t pair = (jj / (kSuperM * kSuperN)) * 8u + xcd;
+        const uint32_t st = pair / n_split;
+        split = pair % n_split;
+        const uint32_t within = jj % (kSuperM * kSuperN);
+        const uint32_t grp = st / per_group, in_grp = st % per_group;
+        row_tile = (grp * group + in_grp % group) * kSuperM + within / kSuperN;
+        col_tile = (in_grp / group) * kSuperN + within % kSuperN;
+    };
+    auto locate = [&](uint32_t L, uint32_t& row_tile, uint32_t& col_tile, uint32_t& split) __attribute__((always_inline)) {
+        locate_unchecked(L, row_tile, col_tile, split);
+        return row_tile < n_rt && col_tile < n_ct;
+    };
+    // A tile number together with what locate() says about it (the divisions in there are done on the
+    // vector unit and take a third of a microsecond: once per tile is enough).
+    struct TileId { uint32_t L, row_tile, col_tile, split; };
+    // first number >= L of this workgroup's sequence that names a tile (L >= total when there is none)
+    auto first_tile_from = [&](uint32_t L) __attribute__((always_inline)) {
+        TileId id{L, 0, 0, 0};
+        if (!WALK) {
+            if (!(id.L < total && locate(id.L, id.row_tile, id.col_tile, id.split))) id.L = total;
+            return id;
+        }
+        while (id.L < total && !locate(id.L, id.row_tile, id.col_tile, id.split)) id.L += gridDim.x;
+        return id;
+    };
+    // its record (one 16-byte load; numbers past the end read record 0, which exists)
+    auto load_rec = [&](const TileId& id) __attribute__((always_inline)) {
+        return a.tile_rec[id.L < total ? id.row_tile : 0u];
+    };
 
-    // split K (second product only): this workgroup multiplies steps [step_lo, step_hi) of the K / 64
-    // and writes its own FP32 partial, which combine_kernel sums in split order
-    const uint32_t n_steps_all = K / kTK;
-    const uint32_t step_lo = uint32_t(uint64_t(n_steps_all) * split / n_split);
-    const uint32_t step_hi = uint32_t(uint64_t(n_steps_all) * (split + 1) / n_split);
-    const uint32_t k_begin = step_lo * kTK;
-
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    const int q = lane & 31, h = lane >> 5;
+    // The lane number as a value the compiler cannot trace back to threadIdx: what the per-tile set-up code
+    // derives from it is then computed again for every tile instead of being held in registers across the
+    // k loop, where registers are short.
+    auto fresh_lane = [&]() __attribute__((always_inline)) {
+        int x = tid;
+        asm volatile("" : "+v"(x));
+        return x & 63;
+    };
     constexpr int kStageBytes = 32768;
     uint8_t* const lds_b8 = reinterpret_cast<uint8_t*>(lds);
-
-    // ---- global sources of this lane's LDS-direct loads (4 for A, 4 for B per step): 32-bit byte
-    // offsets from bases that are uniform over the workgroup
-    const uint8_t* const a_base = reinterpret_cast<const uint8_t*>(MODE == 1 ? a.tokens : a.hbuf) + size_t(k_begin) * 2;
-    uint32_t a_off[kDma];
-#pragma unroll
-    for (int i = 0; i < kDma; ++i) {
-        const int r_lds = 8 * (wave * kDma + i) + (lane >> 3);                 // row of the A tile
-        const int piece = (lane & 7) ^ ((r_lds >> 1) & 7);                  // global 16-byte piece held at position lane & 7
-        const int32_t r = min(r_lds, t.rows - 1);
-        uint32_t row_elems;
-        if (MODE == 1) row_elems = (uint32_t(a.sorted_pair[t.row0 + r]) / a.K) * a.H;
-        else row_elems = uint32_t(t.row0 + r) * a.F;
-        a_off[i] = 2u * (row_elems + 8u * piece);
-    }
     const size_t mat = size_t(a.H) * a.F;
-    const uint8_t* const b_base = reinterpret_cast<const uint8_t*>(
-        MODE == 1 ? a.slots13 + size_t(t.slot) * 2 * mat : a.slots2 + size_t(t.slot) * mat + size_t(k_begin) * N);
-    uint32_t b_off[kDma];
+    const uint32_t n_steps_all = K / kTK;
+
+    // What a tile's loads need: the lane's byte offsets of its LDS-direct loads (kDma for A, kDma for B
+    // per step) from bases that are uniform over the workgroup, the step range, where the results go.
+    struct TileState {
+        uint32_t a_off[kDma], b_off[kDma];   // until finish_state(): a_off = pair numbers of the lane's rows as loaded
+                                             // (first product) or their row numbers (second), b_off unset
+        const uint8_t* a_base;
+        const uint8_t* b_base;
+        int32_t rows, row0;
+        uint32_t n_base, split, n_steps;
+        bool valid;
+    };
+    // rec: the tile's record, loaded earlier.  Issues the gather of the rows' pair numbers (first product);
+    // finish_state() turns them into offsets where the tile's first loads are issued, so that nothing waits
+    // for the gather in between.
+    auto make_state = [&](const TileId& id, const int4& rec, TileState& s) __attribute__((always_inline)) {
+        const uint32_t col_tile = id.col_tile, split = id.split;
+        s.valid = id.L < total;
+        s.rows = __builtin_amdgcn_readfirstlane(rec.z);
+        s.row0 = __builtin_amdgcn_readfirstlane(rec.y);
+        const int32_t slot = __builtin_amdgcn_readfirstlane(rec.w);
+        s.valid = s.valid && s.rows > 0 && slot >= 0;
+        if (!s.valid) { s.rows = 1; s.row0 = 0; }
+        s.n_base = col_tile * ncols_tile;
+        s.split = split;
+        // split K (second product only): this tile multiplies steps [step_lo, step_hi) of the K / 64
+        // and writes its own FP32 partial, which combine_kernel sums in split order
+        const uint32_t step_lo = uint32_t(uint64_t(n_steps_all) * split / n_split);
+        const uint32_t step_hi = uint32_t(uint64_t(n_steps_all) * (split + 1) / n_split);
+        const uint32_t k_begin = step_lo * kTK;
+        s.n_steps = MODE == 1 ? 0u : step_hi - step_lo;        // >= 1: the host keeps ksplit <= K / 64
+        s.a_base = MODE == 1 ? nullptr : reinterpret_cast<const uint8_t*>(a.hbuf) + size_t(k_begin) * 2;
+        const int lane = fresh_lane();
 #pragma unroll
-    for (int i = 0; i < kDma; ++i) {
-        const int k_lds = 2 * (wave * kDma + i) + (lane >> 5);                 // k row of the B tile
-        const int pp = lane & 31;                                           // physical 16-byte piece in the row
-        const int unit = (pp >> 2) ^ (k_lds & 3);                           // logical unit of 32 columns
-        const uint32_t c = 32u * unit + 8u * (pp & 3);                      // column inside the 256-column tile
-        uint32_t elems;
-        if (MODE == 1) elems = (c >= 128 ? uint32_t(mat) : 0u) + min(n_base + (c & 127u), N - 8);
-        else elems = min(n_base + c, N - 8);
-        b_off[i] = 2u * (elems + uint32_t(k_lds) * N);
-    }
+        for (int i = 0; i < kDma; ++i) {
+            const int r_lds = 8 * (wave * kDma + i) + (lane >> 3);                 // row of the A tile
+            const int32_t r = min(r_lds, s.rows - 1);
+            s.a_off[i] = MODE == 1 ? uint32_t(a.sorted_pair[s.row0 + r]) : uint32_t(s.row0 + r);
+        }
+        const size_t slot_u = s.valid ? size_t(slot) : 0u;
+        s.b_base = reinterpret_cast<const uint8_t*>(
+            MODE == 1 ? a.slots13 + slot_u * 2 * mat : a.slots2 + slot_u * mat + size_t(k_begin) * N);
+    };
+    auto finish_state = [&](TileState& s) __attribute__((always_inline)) {
+        const int lane = fresh_lane();
+#pragma unroll
+        for (int i = 0; i < kDma; ++i) {
+            const int r_lds = 8 * (wave * kDma + i) + (lane >> 3);              // row of the A tile
+            const int piece = (lane & 7) ^ ((r_lds >> 1) & 7);                  // global 16-byte piece held at position lane & 7
+            const uint32_t row_elems = MODE == 1 ? (s.a_off[i] / a.K) * a.H : s.a_off[i] * a.F;
+            s.a_off[i] = 2u * (row_elems + 8u * piece);
+        }
+#pragma unroll
+        for (int i = 0; i < kDma; ++i) {
+            const int k_lds = 2 * (wave * kDma + i) + (lane >> 5);                 // k row of the B tile
+            const int pp = lane & 31;                                           // physical 16-byte piece in the row
+            const int unit = (pp >> 2) ^ (k_lds & 3);                           // logical unit of 32 columns
+            const uint32_t c = 32u * unit + 8u * (pp & 3);                      // column inside the 256-column tile
+            uint32_t elems;
+            if (MODE == 1) elems = (c >= 128 ? uint32_t(mat) : 0u) + min(s.n_base + (c & 127u), N - 8);
+            else elems = min(s.n_base + c, N - 8);
+            s.b_off[i] = 2u * (elems + uint32_t(k_lds) * N);
+        }
+    };
     // stage_off: 0 or kStageBytes, uniform.  The load is written as inline assembly on purpose: with
     // the compiler's builtin, every later LDS read waits for all outstanding LDS-direct loads
     // (it cannot see that they go to the other stage), which serialises the whole step.  Here the
-    // only wait is the explicit vmcnt(0) before the step's barrier.
+    // only waits are the explicit ones before the barriers.
     const uint32_t lds_base = uint32_t(uintptr_t((__attribute__((address_space(3))) void*)lds));
     // (M0 carries the LDS destination and is read when the instruction issues; it is a register the
     // compiler reserves, so its previous value is put back.)
@@ -1186,37 +1249,58 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
                      : "=&s"(saved_m0) : "v"(gptr), "s"(lds_addr) : "memory");
     };
     // a_stage_off / b_stage_off: byte offset of the destination stage inside the operand's region, uniform
-    auto dma_a = [&](uint32_t k0, int a_stage_off, int n) __attribute__((always_inline)) {
-        dma16(a_base + size_t(k0) * 2 + a_off[n], lds_base + a_stage_off + (wave * kDma + n) * 1024);
+    auto dma_a = [&](const TileState& s, uint32_t k0, int a_stage_off, int n) __attribute__((always_inline)) {
+        // (the first product never splits K: its A base and step count are the same for every tile)
+        const uint8_t* base = MODE == 1 ? reinterpret_cast<const uint8_t*>(a.tokens) : s.a_base;
+        dma16(base + size_t(k0) * 2 + s.a_off[n], lds_base + a_stage_off + (wave * kDma + n) * 1024);
     };
-    auto dma_b = [&](uint32_t k0, int b_stage_off, int n) __attribute__((always_inline)) {
-        dma16(b_base + size_t((FLUXMOE_D2L_PROBE & 16) ? 0u : k0) * N * 2 + b_off[n], lds_base + 2 * kStageBytes + b_stage_off + (wave * kDma + n) * 1024);
+    auto dma_b = [&](const TileState& s, uint32_t k0, int b_stage_off, int n) __attribute__((always_inline)) {
+        dma16(s.b_base + size_t((FLUXMOE_D2L_PROBE & 16) ? 0u : k0) * N * 2 + s.b_off[n], lds_base + 2 * kStageBytes + b_stage_off + (wave * kDma + n) * 1024);
+    };
+    auto steps_of = [&](const TileState& s) __attribute__((always_inline)) { return MODE == 1 ? n_steps_all : s.n_steps; };
+    // a tile's first loads: A and B of steps 0 and 1 into stages 0 and 1 (B of step 2 is issued by step 0)
+    auto prime = [&](const TileState& s) __attribute__((always_inline)) {
+#pragma unroll
+        for (int n = 0; n < kDma; ++n) { dma_a(s, 0, 0, n); dma_b(s, 0, 0, n); }
+        if (steps_of(s) > 1) {
+#pragma unroll
+            for (int n = 0; n < kDma; ++n) { dma_a(s, kTK, kStageBytes, n); dma_b(s, kTK, kStageBytes, n); }
+        }
     };
 
-    // ---- fragment addresses (bytes from the start of stage 0 of the operand's region)
+    // ---- fragment addresses (bytes from the start of stage 0 of the operand's region); the k loop moves
+    // them from stage to stage, so every tile starts from these values again
     int a_addr[kRowTiles][4];
-#pragma unroll
-    for (int i = 0; i < kRowTiles; ++i) {
-        const int R = wm * kWaveRows + 32 * i + q;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) a_addr[i][ks] = R * 128 + 16 * ((2 * ks + h) ^ ((R >> 1) & 7));
-    }
-    // B fragment j of sub-step ks, read t: row 16 ks + 8 h + 4 t + e, unit u(j) ^ e, bytes 32 nh + 8 g
-    const int e = (lane & 15) >> 2, g = lane & 3, nh = (lane >> 4) & 1;
     int b_addr[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int unit = MODE == 1 ? ((((2 * wn + (j & 1)) ^ e)) + 4 * (j >> 1)) : (4 * wn + (j ^ e));
-        b_addr[j] = 2 * kStageBytes + (8 * h + e) * 512 + 64 * unit + 32 * nh + 8 * g;
-    }
-
     f32x16 acc[kRowTiles][4];
+    int b_next_delta = kStageBytes;
+    int a_own = 0, b_own = 0;                                // byte offsets of the current step's stages
+    auto begin_tile = [&]() __attribute__((always_inline)) {
+        const int lane = fresh_lane();
+        const int q = lane & 31, h = lane >> 5;
+        const int e = (lane & 15) >> 2, g = lane & 3, nh = (lane >> 4) & 1;
 #pragma unroll
-    for (int i = 0; i < kRowTiles; ++i)
+        for (int i = 0; i < kRowTiles; ++i) {
+            const int R = wm * kWaveRows + 32 * i + q;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int ks = 0; ks < 4; ++ks) a_addr[i][ks] = R * 128 + 16 * ((2 * ks + h) ^ ((R >> 1) & 7));
+        }
+        // B fragment j of sub-step ks, read t: row 16 ks + 8 h + 4 t + e, unit u(j) ^ e, bytes 32 nh + 8 g
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        for (int j = 0; j < 4; ++j) {
+            const int unit = MODE == 1 ? ((((2 * wn + (j & 1)) ^ e)) + 4 * (j >> 1)) : (4 * wn + (j ^ e));
+            b_addr[j] = 2 * kStageBytes + (8 * h + e) * 512 + 64 * unit + 32 * nh + 8 * g;
+        }
+#pragma unroll
+        for (int i = 0; i < kRowTiles; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+        b_next_delta = kStageBytes;
+        a_own = 0;
+        b_own = 0;
+    };
 
     bf16x8 fa[2][kRowTiles];
     i16x4 fb_lo[2][4], fb_hi[2][4];
@@ -1224,7 +1308,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     // A tiles, then the two halves (k 0..3 and 4..7 of the lane's 8) of the four B fragments
     // OTHER: read from the next step's stage instead of the one the address registers point at
     // (A: the other of two stages; B: b_next_delta bytes further in its ring of three)
-    int b_next_delta = kStageBytes;
     auto lfrag_item = [&](int other, int ks, int set, int n) __attribute__((always_inline)) {
         if (n < kRowTiles) {
             fa[set][n] = *reinterpret_cast<const bf16x8*>(lds_b8 + (a_addr[n][ks] ^ (other ? kStageBytes : 0)));
@@ -1242,7 +1325,6 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], __builtin_bit_cast(bf16x8, full), acc[i][j], 0, 0, 0);
     };
 
-    const uint32_t n_steps = step_hi - step_lo;                // >= 1: the host keeps ksplit <= K / 64
     // Step s multiplies A stage s % 2 and B stage s % 3.  After its barrier nobody reads those
     // stages any more, so sub-step 3 issues the A loads of step s + 2 into the same A stage and
     // sub-step 0 of the next step issues the B loads of step s + 3 into the same B stage: B, whose
@@ -1250,9 +1332,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     // Loads return in order, so waiting until at most 4 are outstanding before the barrier of
     // step s leaves only the B loads of step s + 2 in flight.
     // LOAD_B: B of step s + 2 (issued in sub-step 0); LOAD_A: A of step s + 2 (after the barrier);
-    // NEXT: another step follows.
-    int a_own = 0, b_own = 0;                                // byte offsets of this step's stages
-    auto step = [&](uint32_t k0, auto LOAD_B, auto LOAD_A, auto NEXT, auto ACT) __attribute__((always_inline)) {
+    // NEXT: another step follows.  After the barrier of a tile's last step all five stages are free: that
+    // step issues the first loads of the workgroup's next tile (`upcoming`, if it has one) behind its last
+    // MFMAs, and they travel while the epilogue runs.
+    auto step = [&](const TileState& cur, TileState& upcoming, uint32_t k0, auto LOAD_B, auto LOAD_A, auto NEXT, auto ACT) __attribute__((always_inline)) {
         const int b_plus2 = b_own >= kStageBytes ? b_own - kStageBytes : b_own + 2 * kStageBytes;   // stage of step s + 2
         // one sub-step: the MFMAs of register set `set`, between them the fragment reads of sub-step
         // next_ks into the other set (other = 1: from the next step's stages) and this step's share of loads
@@ -1261,8 +1344,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
             for (int n = 0; n < kMfma; ++n) {
                 if (ACT.value) mfma_item(set, n);
                 if (READ.value && ACT.value && n < kFrag && !(FLUXMOE_D2L_PROBE & 1)) lfrag_item(other, next_ks, set ^ 1, n);
-                if (DMA_B.value && (n & 1) && !(FLUXMOE_D2L_PROBE & 4)) dma_b(k0 + 2 * kTK, b_plus2, n >> 1);
-                if (DMA_A.value && (n & 1) && !(FLUXMOE_D2L_PROBE & 2)) dma_a(k0 + 2 * kTK, a_own, n >> 1);
+                if (DMA_B.value && (n & 1) && !(FLUXMOE_D2L_PROBE & 4)) dma_b(cur, k0 + 2 * kTK, b_plus2, n >> 1);
+                if (DMA_A.value && (n & 1) && !(FLUXMOE_D2L_PROBE & 2)) dma_a(cur, k0 + 2 * kTK, a_own, n >> 1);
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (READ.value && ACT.value && !(FLUXMOE_D2L_PROBE & 1)) {
@@ -1282,6 +1365,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
         }
         __syncthreads();                                      // all reads of this step's stages are in registers
         sub(1, 1, 0, NEXT, F{}, LOAD_A);                      // sub-step 3
+        if (WALK && !NEXT.value && upcoming.valid) { finish_state(upcoming); prime(upcoming); }
         // advance to the next step's stages
 #pragma unroll
         for (int i = 0; i < kRowTiles; ++i)
@@ -1296,35 +1380,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     using Yes = std::integral_constant<bool, true>;
     using No = std::integral_constant<bool, false>;
 
-    // prologue: A of steps 0 and 1, B of steps 0 and 1 (B of step 2 is issued by step 0)
-#pragma unroll
-    for (int n = 0; n < kDma; ++n) { dma_a(0, 0, n); dma_b(0, 0, n); }
-    if (n_steps > 1) {
-#pragma unroll
-        for (int n = 0; n < kDma; ++n) { dma_a(kTK, kStageBytes, n); dma_b(kTK, kStageBytes, n); }
-    }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    // A wavefront whose 64 rows all lie past the tile's last row (tail tiles of an expert) takes part
-    // in the loads and barriers only: with at most 128 rows every SIMD runs one multiplying wavefront
-    // instead of two.
-    auto k_loop = [&](auto ACT) __attribute__((always_inline)) {
-        if (ACT.value) {
-#pragma unroll
-            for (int n = 0; n < kFrag; ++n) lfrag_item(0, 0, 0, n);
-            if (FLUXMOE_D2L_PROBE & 1) {
-#pragma unroll
-                for (int n = 0; n < kFrag; ++n) lfrag_item(0, 1, 1, n);
-            }
-        }
-        uint32_t s = 0;
-        for (; s + 2 < n_steps; ++s) step(s * kTK, Yes{}, Yes{}, Yes{}, ACT);
-        if (s + 1 < n_steps) step(s * kTK, No{}, No{}, Yes{}, ACT);
-        step(0, No{}, No{}, No{}, ACT);
-    };
-    if (wm * kWaveRows < t.rows) k_loop(Yes{}); else k_loop(No{});
-    if (FLUXMOE_D2L_PROBE & 8) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); }
-
+    auto epilogue = [&](const TileState& c) __attribute__((always_inline)) {
+    const int lane = fresh_lane();
+    const int q = lane & 31, h = lane >> 5;
     // epilogue.  D layout of the 32x32 MFMA: column q = lane % 32, rows 8 (r / 4) + 4 (lane / 32) + r % 4;
     // fragment j of this wavefront holds tile columns 128 wn + 32 j + q (MODE 2) or, in MODE 1,
     // gate (j = 0, 1) and up (j = 2, 3) of h columns 64 wn + 32 (j & 1) + q
@@ -1334,11 +1392,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
         // stores instead of 2-byte ones
         // v_perm_b32(other, own, sel): selector bytes 0..3 pick from own, 4..7 from other
         const uint32_t pair_sel = (q & 1) ? 0x03020706u : 0x05040100u;
+        // one 64-bit address per stored row; the two column groups of a row lie 64 bytes apart
+        const uint32_t col0 = c.n_base + 64u * wn + (q & ~1);
+        uint16_t* const hlane = a.hbuf + size_t(c.row0) * a.F + col0;
 #pragma unroll
         for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
             for (int r = 0; r < 16; r += 2) {
                 const int32_t row = wm * kWaveRows + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3) + (q & 1);
+                uint16_t* const hrow = hlane + size_t(uint32_t(row)) * a.F;
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     // own = (row r, row r + 1) of this lane's column; the neighbouring lane's pair comes by DPP
@@ -1348,25 +1410,101 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
                                                        swiglu(acc[i][j][r + 1], acc[i][j + 2][r + 1]));
                     const uint32_t other = uint32_t(__builtin_amdgcn_update_dpp(0, int(own), 0xB1, 0xF, 0xF, true));
                     const uint32_t packed = __builtin_amdgcn_perm(other, own, pair_sel);
-                    const uint32_t col = n_base + 64u * wn + 32u * j + (q & ~1);
-                    if (row < t.rows && col < N)
-                        *reinterpret_cast<uint32_t*>(a.hbuf + size_t(t.row0 + row) * a.F + col) = packed;
+                    if (row < c.rows && col0 + 32u * j < N)
+                        *reinterpret_cast<uint32_t*>(hrow + 32 * j) = packed;
                 }
             }
     } else {
+        // one 64-bit address per stored row; the four column groups of a row lie 128 bytes apart
+        const uint32_t col0 = c.n_base + 128u * wn + q;
+        float* const ylane = a.ybuf + (size_t(c.split) * a.pairs_cap + size_t(c.row0)) * a.H + col0;
 #pragma unroll
         for (int i = 0; i < kRowTiles; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int32_t row = wm * kWaveRows + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-                if (row >= t.rows) continue;
+                if (row >= c.rows) continue;
+                float* const yrow = ylane + size_t(uint32_t(row)) * a.H;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const uint32_t col = n_base + 128u * wn + 32u * j + q;
-                    if (col >= N) continue;
-                    a.ybuf[(size_t(split) * a.pairs_cap + size_t(t.row0 + row)) * a.H + col] = acc[i][j][r];
+                    if (col0 + 32u * j >= N) continue;
+                    yrow[32 * j] = acc[i][j][r];
                 }
             }
+    }
+    };
+
+    // A wavefront whose 64 rows all lie past the tile's last row (tail tiles of an expert) takes part
+    // in the loads and barriers only: with at most 128 rows every SIMD runs one multiplying wavefront
+    // instead of two.
+    auto k_loop = [&](const TileState& cur, TileState& upcoming, auto ACT) __attribute__((always_inline)) {
+        if (ACT.value) {
+#pragma unroll
+            for (int n = 0; n < kFrag; ++n) lfrag_item(0, 0, 0, n);
+            if (FLUXMOE_D2L_PROBE & 1) {
+#pragma unroll
+                for (int n = 0; n < kFrag; ++n) lfrag_item(0, 1, 1, n);
+            }
+        }
+        uint32_t s = 0;
+        const uint32_t n_steps = steps_of(cur);
+        for (; s + 2 < n_steps; ++s) step(cur, upcoming, s * kTK, Yes{}, Yes{}, Yes{}, ACT);
+        if (s + 1 < n_steps) step(cur, upcoming, s * kTK, No{}, No{}, Yes{}, ACT);
+        step(cur, upcoming, 0, No{}, No{}, No{}, ACT);
+    };
+
+    // ---- the workgroup's tiles.  Three of them are in the pipeline: `cur` is multiplied; `nxt` has had its
+    // record read and its row gather issued (the values are first touched when its loads are issued at the
+    // end of cur's k loop); the record of the one after is on its way.
+    // (the record of the workgroup's own number is requested before anything looks at the tile count, which
+    // is itself a load: the two travel together instead of one after the other)
+    int4 rec_own;
+    {
+        TileId own{blockIdx.x, 0, 0, 0};
+        uint32_t c, sp;
+        locate_unchecked(own.L, own.row_tile, c, sp);
+        rec_own = a.tile_rec[min(own.row_tile, a.tiles_cap - 1u)];
+    }
+    const TileId none{total, 0, 0, 0};
+    TileId id_cur = first_tile_from(blockIdx.x);
+    TileId id_nxt = WALK ? first_tile_from(id_cur.L < total ? id_cur.L + gridDim.x : total) : none;
+    int4 rec_nxt = WALK ? load_rec(id_nxt) : make_int4(0, 0, 0, -1);
+    TileState cur, nxt;
+    make_state(id_cur, id_cur.L == blockIdx.x ? rec_own : load_rec(id_cur), cur);
+    nxt.valid = false;
+    bool primed = false;                                     // cur's first loads were issued by the tile before it
+    while (id_cur.L < total) {
+        TileId id_after = none;
+        int4 rec_after = make_int4(0, 0, 0, -1);
+        if (WALK) {
+            id_after = first_tile_from(id_nxt.L < total ? id_nxt.L + gridDim.x : total);
+            rec_after = load_rec(id_after);                 // the one load between cur's first loads and the wait below
+        }
+        // The upcoming tile's row gather is issued here, a whole k loop before its values are needed: issued
+        // later (between the steady steps and the last two) the in-order wait of the next step stalls on it
+        // (measured: 10 % of the first product's time).
+        if (WALK) make_state(id_nxt, rec_nxt, nxt);
+        if (cur.valid) {
+            begin_tile();
+            if (!primed) {
+                finish_state(cur);
+                prime(cur);
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            } else {
+                // loads return in order: cur's first loads are older than the record load and the gather just issued
+                asm volatile("s_waitcnt vmcnt(%0)" :: "n"(MODE == 1 ? 1 + kDma : 1) : "memory");
+            }
+            __syncthreads();
+            if (wm * kWaveRows < cur.rows) k_loop(cur, nxt, Yes{}); else k_loop(cur, nxt, No{});
+            if (FLUXMOE_D2L_PROBE & 8) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); __syncthreads(); }
+            epilogue(cur);
+        }
+        if (!WALK) break;
+        primed = cur.valid && nxt.valid;
+        cur = nxt;
+        id_cur = id_nxt;
+        id_nxt = id_after;
+        rec_nxt = rec_after;
     }
 }
 
@@ -1490,16 +1628,16 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_tiled4_kernel<2>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, int(lds_bytes));
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<1, 8>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<1, 8, true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<2, 8>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<2, 8, false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<1, 4>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<1, 4, false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
             if (e != hipSuccess) return e;
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<2, 4>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_d2l_kernel<2, 4, false>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 163840);
             if (e != hipSuccess) return e;
             attr_set = true;
@@ -1511,14 +1649,28 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
             const uint32_t supers = (n_sm * n_sn * n_split + 7) / 8 * 8;      // whole rounds over the 8 XCDs
             return dim3(supers * kSuperM * kSuperN, 1, 1);
         };
-        if (d2l4) hipLaunchKernelGGL((gemm_d2l_kernel<1, 4>), grid_for((a.F + 127) / 128), dim3(256), 163840, stream, a);
-        else if (d2l) hipLaunchKernelGGL((gemm_d2l_kernel<1, 8>), grid_for((a.F + 127) / 128), dim3(512), 163840, stream, a);
+        // LDS-direct kernels: the launch covers `tiled_total` tile numbers; a workgroup walks through the numbers
+        // blockIdx.x, + gridDim.x, ... and overlaps a tile's epilogue with the next one's first loads.  One
+        // workgroup fits on a CU, so the first product runs tiled_persist x 256 workgroups (a multiple of 256
+        // keeps a workgroup's numbers on its XCD); with tiled_persist = 0, and for the second product, one
+        // workgroup per number.  The fixed hand-out loses when the last column block of a super-tile row is
+        // partly empty (workgroups with no tile there idle): measured on H 5120 / F 1536, 2048 rows per expert,
+        // the first product gains 7 % (its tiles are short: 80 steps, and each needs a row gather first), the
+        // second, whose 20 column tiles leave half of every third block empty, loses 11 %; on H 4096 / F 14336
+        // both change by under 1 %.
+        auto d2l_grid = [&](const dim3& all, bool walk) {
+            a.tiled_total = all.x;
+            const uint32_t cap = a.tiled_persist * 256u;
+            return (walk && a.tiled_persist && all.x > cap) ? dim3(cap, 1, 1) : all;
+        };
+        if (d2l4) { const dim3 g = d2l_grid(grid_for((a.F + 127) / 128), true); hipLaunchKernelGGL((gemm_d2l_kernel<1, 4, false>), g, dim3(256), 163840, stream, a); }
+        else if (d2l) { const dim3 g = d2l_grid(grid_for((a.F + 127) / 128), true); hipLaunchKernelGGL((gemm_d2l_kernel<1, 8, true>), g, dim3(512), 163840, stream, a); }
         else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<1>, grid_for((a.F + 127) / 128), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), lds_bytes, stream, a);
         mark(2, 0);
         mark(3, 1);
-        if (d2l4) hipLaunchKernelGGL((gemm_d2l_kernel<2, 4>), grid_for((a.H + 255) / 256, a.ksplit), dim3(256), 163840, stream, a);
-        else if (d2l) hipLaunchKernelGGL((gemm_d2l_kernel<2, 8>), grid_for((a.H + 255) / 256, a.ksplit), dim3(512), 163840, stream, a);
+        if (d2l4) { const dim3 g = d2l_grid(grid_for((a.H + 255) / 256, a.ksplit), false); hipLaunchKernelGGL((gemm_d2l_kernel<2, 4, false>), g, dim3(256), 163840, stream, a); }
+        else if (d2l) { const dim3 g = d2l_grid(grid_for((a.H + 255) / 256, a.ksplit), false); hipLaunchKernelGGL((gemm_d2l_kernel<2, 8, false>), g, dim3(512), 163840, stream, a); }
         else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<2>, grid_for((a.H + 255) / 256), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), lds_bytes, stream, a);
         mark(3, 0);

@@ -112,6 +112,7 @@ struct fluxmoe_ctx {
     int tune_blocks_per_wave = 3;
     int tune_tiled_waves = 2;             // FLUXMOE_FFN_TILED_WAVES: 2 = LDS-direct loads (default), 8 = register-staged,
                                           // 4 = register-staged with four wavefronts of 128 x 128
+    int tune_tiled_persist = 1;           // FLUXMOE_FFN_TILED_PERSIST: 0 = one workgroup per tile, n = n x 256 workgroups walking the tiles
     int tune_tiled_group = 0;             // FLUXMOE_FFN_TILED_GROUP: 1..8 super-rows per group of the tiled gate/up kernel, 0 = from the shape
     // optional kernel timing (fluxmoe_profile_*)
     bool profiling = false;
@@ -367,6 +368,10 @@ int fluxmoe_create(const fluxmoe_desc* desc, fluxmoe_ctx** out_ctx) {
     if (const char* v = std::getenv("FLUXMOE_FFN_TILED_WAVES")) {
         const int w = std::atoi(v);
         if (w == 1 || w == 2 || w == 4 || w == 8) c->tune_tiled_waves = w;
+    }
+    if (const char* v = std::getenv("FLUXMOE_FFN_TILED_PERSIST")) {
+        const int w = std::atoi(v);
+        if (w >= 0 && w <= 16) c->tune_tiled_persist = w;
     }
     if (const char* v = std::getenv("FLUXMOE_FFN_TILED_GROUP")) {
         const int w = std::atoi(v);
@@ -1075,6 +1080,7 @@ static int expert_ffn_enqueue(fluxmoe_ctx* c, uint32_t layer, const uint16_t* to
     a.pairs_cap = p.pairs_cap; a.tiles_cap = p.tiles_cap; a.m_tile = p.m_tile; a.ksplit = p.ksplit;
     a.tiled_waves = c->tune_tiled_waves;
     a.tiled_group = uint32_t(c->tune_tiled_group);
+    a.tiled_persist = uint32_t(c->tune_tiled_persist);
 
     if (c->load_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_load[layer], 0));
     if (c->rel_valid[layer]) HIPCHECK(hipStreamWaitEvent(stream, c->ev_rel[layer], 0));
@@ -1161,6 +1167,7 @@ int fluxmoe_shared_expert_ffn(fluxmoe_ctx* c, const uint16_t* w13, const uint16_
     a.pairs_cap = p.pairs_cap; a.tiles_cap = p.tiles_cap; a.m_tile = p.m_tile; a.ksplit = p.ksplit;
     a.tiled_waves = c->tune_tiled_waves;
     a.tiled_group = uint32_t(c->tune_tiled_group);
+    a.tiled_persist = uint32_t(c->tune_tiled_persist);
     HIPCHECK(launch_ffn(a, c->n_cus, stream, c->profiling ? ffn_span_hook : nullptr, c));
     return FLUXMOE_OK;
 }

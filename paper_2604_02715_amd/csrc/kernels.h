@@ -110,6 +110,9 @@ struct FfnArgs {
     uint32_t pairs_cap, tiles_cap, m_tile, ksplit;
     uint32_t tiled_waves;        // variant of the LDS-tiled kernels (m_tile 256): 2 LDS-direct loads, 8 or 4
                                  // wavefronts with register-staged loads
+    uint32_t tiled_persist;      // LDS-direct kernels: workgroups per CU-sized round that walk through the tiles (1 = 256
+                                 // workgroups), 0 = one workgroup per tile
+    uint32_t tiled_total;        // set per launch by launch_ffn: tile numbers of the LDS-direct kernel's launch
     uint32_t tiled_group;        // super-rows of the LDS-direct gate/up kernel that share a column block in time;
                                  // 0 = launch_ffn derives it from the rows per expert
 };

@@ -140,6 +140,11 @@ def test_tile_order_of_the_tiled_gate_up_kernel_does_not_change_results(monkeypa
         assert np.array_equal(run_ffn_case(cfg, seed=2), base), group
     monkeypatch.delenv("FLUXMOE_FFN_TILED_GROUP")
     assert np.array_equal(run_ffn_case(cfg, seed=2), base)
+    # FLUXMOE_FFN_TILED_PERSIST: 0 = one workgroup per tile number of the gate/up kernel, n = n x 256 workgroups
+    # that each walk through several numbers (512 numbers here: two per workgroup with the default 1)
+    for persist in ("0", "2"):
+        monkeypatch.setenv("FLUXMOE_FFN_TILED_PERSIST", persist)
+        assert np.array_equal(run_ffn_case(cfg, seed=2), base), persist
 
 
 def test_wave_mode_accumulates_to_the_single_shot_result():
