@@ -140,7 +140,7 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
         if (e >= 0) atomicAdd(&count[e], 1);
     }
     __syncthreads();
-    // Tiles per class over all experts, needed before the first round's tiles can be numbered.  With one
+    // Tiles per class over all experts, needed before the tiles of the first 1024 experts can be numbered.  With one
     // round (at most 1024 experts) the round's own scan delivers them; otherwise they are summed here
     // (integer sums: the order of the additions does not matter).
     const bool one_round = a.E <= 1024;
