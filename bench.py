@@ -254,7 +254,7 @@ def decode_kernel_source_hash():
     """sha256 over the sources the decode kernel is compiled from."""
     import hashlib
     h = hashlib.sha256()
-    for name in ("decode_kernel.hip", "kernels.h"):
+    for name in ("decode_kernel.hip", "decode_args.h"):
         h.update(open(os.path.join(ROOT, "paper_2604_02715_amd", "csrc", name), "rb").read())
     return h.hexdigest()
 

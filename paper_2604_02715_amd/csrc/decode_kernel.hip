@@ -29,7 +29,7 @@
 #include <cstddef>
 #include <cstring>
 
-#include "kernels.h"
+#include "decode_args.h"
 
 namespace fluxmoe {
 
