@@ -1109,7 +1109,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     const uint32_t ncols_tile = MODE == 1 ? 128u : 256u;
     const uint32_t n_ct = (N + ncols_tile - 1) / ncols_tile;
     const uint32_t n_rt = uint32_t(a.n_tiles[0]);
-    const uint32_t n_sn = (n_ct + kSuperN - 1) / kSuperN;
+    // Super-tile of this launch: 32 tiles (one per CU of an XCD) as sm rows x sn columns, sn a power of two
+    // chosen by the launcher so that the column tiles fill whole super-tiles where they can.
+    const uint32_t sn_log2 = a.tiled_sn_log2, sn = 1u << sn_log2, sm = 32u >> sn_log2;
+    const uint32_t n_sn = (n_ct + sn - 1) >> sn_log2;
     // Workgroups go to the 8 XCDs round robin, so (super-tile, K split) pair number p runs on XCD
     // p % 8: the splits of one super-tile land on different XCDs
     const uint32_t n_split = MODE == 2 ? a.ksplit : 1u;
@@ -1118,7 +1121,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     // so the expert's weights for that column block leave HBM once and the other XCDs find them in the
     // memory-side cache, while the group's activations stay there across the column blocks.
     // (The second product has two column blocks at most and measured no gain: it keeps super-row order.)
-    const uint32_t group = MODE == 1 ? a.tiled_group : 1u;
+    const uint32_t group = a.tiled_group;
     const uint32_t per_group = group * n_sn;
     // Tile number L -> (row tile, column tile, K split); false when the number names no tile.  A workgroup
     // takes the numbers blockIdx.x, blockIdx.x + gridDim.x, ...; gridDim.x is a multiple of 256 (or covers
@@ -1127,13 +1130,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
     const uint32_t total = a.tiled_total;
     auto locate_unchecked = [&](uint32_t L, uint32_t& row_tile, uint32_t& col_tile, uint32_t& split) __attribute__((always_inline)) {
         const uint32_t xcd = L % 8u, jj = L / 8u;
-        const uint32_t pair = (jj / (kSuperM * kSuperN)) * 8u + xcd;
+        const uint32_t pair = (jj / 32u) * 8u + xcd;
         const uint32_t st = pair / n_split;
         split = pair % n_split;
-        const uint32_t within = jj % (kSuperM * kSuperN);
+        const uint32_t within = jj % 32u;
         const uint32_t grp = st / per_group, in_grp = st % per_group;
-        row_tile = (grp * group + in_grp % group) * kSuperM + within / kSuperN;
-        col_tile = (in_grp / group) * kSuperN + within % kSuperN;
+        row_tile = (grp * group + in_grp % group) * sm + (within >> sn_log2);
+        col_tile = (in_grp / group) * sn + (within & (sn - 1u));
     };
     auto locate = [&](uint32_t L, uint32_t& row_tile, uint32_t& col_tile, uint32_t& split) __attribute__((always_inline)) {
         locate_unchecked(L, row_tile, col_tile, split);
@@ -1593,11 +1596,6 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
     (void)n_cus;
     if (args.T == 0) return hipSuccess;
     FfnArgs a = args;
-    {   // super-rows (4 row tiles of 256) that an expert fills on average, between 1 and 8 (one per XCD)
-        const uint64_t pairs = uint64_t(a.T) * a.K;
-        const uint64_t avg = pairs / std::max<uint64_t>(1, std::min<uint64_t>(a.E, pairs));
-        a.tiled_group = uint32_t(std::min<uint64_t>(8, std::max<uint64_t>(1, args.tiled_group ? args.tiled_group : (avg + 512) / 1024)));
-    }
     auto mark = [&](int kind, int begin) { if (hook) hook(user, kind, begin, stream); };
     const size_t sh = (3 * size_t(a.E) + 1024) * sizeof(int32_t);
     mark(1, 1);
@@ -1643,11 +1641,38 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
             attr_set = true;
         }
         mark(2, 1);
-        auto grid_for = [&](uint32_t n_ct, uint32_t n_split = 1) {
-            const uint32_t n_sm = ((a.tiles_cap + kSuperM - 1) / kSuperM + a.tiled_group - 1) / a.tiled_group * a.tiled_group;
+        // register-staged kernels: super-tiles of 4 x 8 tiles, super-row order
+        auto grid_for = [&](uint32_t n_ct) {
+            const uint32_t n_sm = (a.tiles_cap + kSuperM - 1) / kSuperM;
             const uint32_t n_sn = (n_ct + kSuperN - 1) / kSuperN;
-            const uint32_t supers = (n_sm * n_sn * n_split + 7) / 8 * 8;      // whole rounds over the 8 XCDs
+            const uint32_t supers = (n_sm * n_sn + 7) / 8 * 8;                // whole rounds over the 8 XCDs
             return dim3(supers * kSuperM * kSuperN, 1, 1);
+        };
+        // LDS-direct kernels.  A launch whose workgroups walk through the tiles takes as the super-tile's
+        // column count the power of two (8, 4, 16, 2 in that order of preference) that leaves the fewest empty
+        // places in the last column block: a workgroup whose place is empty there has nothing to do while the
+        // others work (H 5120 / F 1536, 12 column tiles of the first product: 4 x 8 super-tiles 10.2 ms,
+        // 8 x 4 8.1 ms at 2048 rows per expert).  With one workgroup per tile the dispatcher fills the holes
+        // and 4 x 8 measured best.  A group is about one expert's super-rows (first product only; at most 8,
+        // one per XCD).  Sets the launch's fields in `a`.
+        const uint64_t pairs_all = uint64_t(a.T) * a.K;
+        const uint64_t avg_rows = pairs_all / std::max<uint64_t>(1, std::min<uint64_t>(a.E, pairs_all));
+        auto d2l_all = [&](uint32_t n_ct, uint32_t n_split, bool grouped, bool walk) {
+            uint32_t best_log2 = 3, best_pad = ~0u;
+            for (uint32_t lg : {3u, 2u, 4u, 1u}) {
+                if (!walk && lg != 3u) continue;
+                const uint32_t pad = ((n_ct + (1u << lg) - 1) >> lg << lg) - n_ct;
+                if (pad < best_pad) { best_pad = pad; best_log2 = lg; }
+            }
+            a.tiled_sn_log2 = best_log2;
+            const uint32_t sm = 32u >> best_log2;
+            const uint64_t per_super_row = 256ull * sm;
+            a.tiled_group = !grouped ? 1u : uint32_t(std::min<uint64_t>(8, std::max<uint64_t>(1,
+                args.tiled_group ? args.tiled_group : (avg_rows + per_super_row / 2) / per_super_row)));
+            const uint32_t n_sm = ((a.tiles_cap + sm - 1) / sm + a.tiled_group - 1) / a.tiled_group * a.tiled_group;
+            const uint32_t n_sn = (n_ct + (1u << best_log2) - 1) >> best_log2;
+            const uint32_t supers = (n_sm * n_sn * n_split + 7) / 8 * 8;      // whole rounds over the 8 XCDs
+            return dim3(supers * 32u, 1, 1);
         };
         // LDS-direct kernels: the launch covers `tiled_total` tile numbers; a workgroup walks through the numbers
         // blockIdx.x, + gridDim.x, ... and overlaps a tile's epilogue with the next one's first loads.  One
@@ -1663,14 +1688,14 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
             const uint32_t cap = a.tiled_persist * 256u;
             return (walk && a.tiled_persist && all.x > cap) ? dim3(cap, 1, 1) : all;
         };
-        if (d2l4) { const dim3 g = d2l_grid(grid_for((a.F + 127) / 128), true); hipLaunchKernelGGL((gemm_d2l_kernel<1, 4, false>), g, dim3(256), 163840, stream, a); }
-        else if (d2l) { const dim3 g = d2l_grid(grid_for((a.F + 127) / 128), true); hipLaunchKernelGGL((gemm_d2l_kernel<1, 8, true>), g, dim3(512), 163840, stream, a); }
+        if (d2l4) { const dim3 g = d2l_grid(d2l_all((a.F + 127) / 128, 1, true, false), false); hipLaunchKernelGGL((gemm_d2l_kernel<1, 4, false>), g, dim3(256), 163840, stream, a); }
+        else if (d2l) { const dim3 g = d2l_grid(d2l_all((a.F + 127) / 128, 1, true, a.tiled_persist != 0), true); hipLaunchKernelGGL((gemm_d2l_kernel<1, 8, true>), g, dim3(512), 163840, stream, a); }
         else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<1>, grid_for((a.F + 127) / 128), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<1>, grid_for((a.F + 127) / 128), dim3(512), lds_bytes, stream, a);
         mark(2, 0);
         mark(3, 1);
-        if (d2l4) { const dim3 g = d2l_grid(grid_for((a.H + 255) / 256, a.ksplit), false); hipLaunchKernelGGL((gemm_d2l_kernel<2, 4, false>), g, dim3(256), 163840, stream, a); }
-        else if (d2l) { const dim3 g = d2l_grid(grid_for((a.H + 255) / 256, a.ksplit), false); hipLaunchKernelGGL((gemm_d2l_kernel<2, 8, false>), g, dim3(512), 163840, stream, a); }
+        if (d2l4) { const dim3 g = d2l_grid(d2l_all((a.H + 255) / 256, a.ksplit, false, false), false); hipLaunchKernelGGL((gemm_d2l_kernel<2, 4, false>), g, dim3(256), 163840, stream, a); }
+        else if (d2l) { const dim3 g = d2l_grid(d2l_all((a.H + 255) / 256, a.ksplit, false, false), false); hipLaunchKernelGGL((gemm_d2l_kernel<2, 8, false>), g, dim3(512), 163840, stream, a); }
         else if (four) hipLaunchKernelGGL(gemm_tiled4_kernel<2>, grid_for((a.H + 255) / 256), dim3(256), lds_bytes, stream, a);
         else hipLaunchKernelGGL(gemm_tiled_kernel<2>, grid_for((a.H + 255) / 256), dim3(512), lds_bytes, stream, a);
         mark(3, 0);

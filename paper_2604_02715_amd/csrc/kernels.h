@@ -35,6 +35,7 @@ struct FfnArgs {
                                  // wavefronts with register-staged loads
     uint32_t tiled_persist;      // LDS-direct kernels: workgroups per CU-sized round that walk through the tiles (1 = 256
                                  // workgroups), 0 = one workgroup per tile
+    uint32_t tiled_sn_log2;      // set per launch by launch_ffn: log2 of the columns of the LDS-direct kernels' super-tile
     uint32_t tiled_total;        // set per launch by launch_ffn: tile numbers of the LDS-direct kernel's launch
     uint32_t tiled_group;        // super-rows of the LDS-direct gate/up kernel that share a column block in time;
                                  // 0 = launch_ffn derives it from the rows per expert

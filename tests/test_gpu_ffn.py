@@ -145,6 +145,12 @@ def test_tile_order_of_the_tiled_gate_up_kernel_does_not_change_results(monkeypa
     for persist in ("0", "2"):
         monkeypatch.setenv("FLUXMOE_FFN_TILED_PERSIST", persist)
         assert np.array_equal(run_ffn_case(cfg, seed=2), base), persist
+    monkeypatch.delenv("FLUXMOE_FFN_TILED_PERSIST")
+    # the other variants of the tiled kernels at this size (more tile numbers than CUs); same sums in the same
+    # order up to the grouping of partial products inside an MFMA
+    for variant in ("1", "8", "4"):
+        monkeypatch.setenv("FLUXMOE_FFN_TILED_WAVES", variant)
+        assert offn.rel_frobenius(run_ffn_case(cfg, seed=2), base) < 1e-5, variant
 
 
 def test_wave_mode_accumulates_to_the_single_shot_result():
