@@ -153,6 +153,17 @@ def test_tile_order_of_the_tiled_gate_up_kernel_does_not_change_results(monkeypa
         assert offn.rel_frobenius(run_ffn_case(cfg, seed=2), base) < 1e-5, variant
 
 
+@pytest.mark.parametrize("ffn", [640, 384, 2048])
+def test_super_tile_shapes_of_the_walking_gate_up_kernel(ffn):
+    """The workgroups of the LDS-tiled gate/up kernel walk through the tile numbers of super-tiles whose shape
+    the launcher picks from the number of column tiles: 5 column tiles (ffn 640) give 16 x 2 super-tiles with
+    one empty place per row, 3 (ffn 384) 8 x 4 with one empty column, 16 (ffn 2048) the 4 x 8 default.  9000
+    rows in two experts are 37 row tiles: more tile numbers than workgroups in every shape, a partly filled
+    last super-row, tail tiles with few rows."""
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], tokens=9000, top_k=1, n_experts=2, n_slots=2, hidden=128, ffn=ffn)
+    run_ffn_case(cfg, seed=6)
+
+
 def test_wave_mode_accumulates_to_the_single_shot_result():
     cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_slots=3)
     from oracle import paging
