@@ -95,6 +95,53 @@ __device__ __forceinline__ void block_scan_excl(const int32_t (&v)[N], int32_t (
     __syncthreads();
 }
 
+// Large batches: one workgroup per chunk of kRouteChunkPairs pairs counts its pairs per expert
+// (route_count_kernel), the single workgroup of route_sort_kernel<true> adds the chunks up, turns each
+// chunk's count into the chunk's first position inside the expert's rows and does the scans and the tile
+// records, and one workgroup per chunk puts its pairs in place (route_scatter_kernel).  The positions a
+// chunk's pairs get depend only on the chunk, not on which workgroup runs first.
+__device__ __forceinline__ int32_t route_classify(const FfnArgs& a, int32_t e, const int32_t* slot_of, bool report) {
+    if (e < 0 || uint32_t(e) >= a.E) {
+        if (report) atomicOr(a.error_word, 2u);
+        return -1;
+    }
+    if (slot_of[e] < 0) {
+        if (report && !(a.flags & 2u)) atomicOr(a.error_word, 2u);
+        return -1;
+    }
+    return e;
+}
+
+__global__ __launch_bounds__(1024) void route_count_kernel(FfnArgs a) {
+    extern __shared__ int32_t sh[];          // count[E]
+    const uint32_t pairs = a.T * a.K, first = blockIdx.x * kRouteChunkPairs;
+    for (uint32_t e = threadIdx.x; e < a.E; e += 1024) sh[e] = 0;
+    __syncthreads();
+    for (uint32_t p = first + threadIdx.x; p < min(pairs, first + kRouteChunkPairs); p += 1024) {
+        const int32_t e = route_classify(a, a.topk_ids[p], a.page_table, true);
+        if (e >= 0) atomicAdd(&sh[e], 1);
+    }
+    __syncthreads();
+    for (uint32_t e = threadIdx.x; e < a.E; e += 1024) a.chunk_count[size_t(blockIdx.x) * a.E + e] = sh[e];
+}
+
+__global__ __launch_bounds__(1024) void route_scatter_kernel(FfnArgs a) {
+    extern __shared__ int32_t sh[];          // cursor[E]
+    const uint32_t pairs = a.T * a.K, first = blockIdx.x * kRouteChunkPairs;
+    for (uint32_t e = threadIdx.x; e < a.E; e += 1024) sh[e] = a.expert_offset[e] + a.chunk_count[size_t(blockIdx.x) * a.E + e];
+    __syncthreads();
+    for (uint32_t p = first + threadIdx.x; p < min(pairs, first + kRouteChunkPairs); p += 1024) {
+        const int32_t e = route_classify(a, a.topk_ids[p], a.page_table, false);
+        int32_t pos = -1;
+        if (e >= 0) {
+            pos = atomicAdd(&sh[e], 1);
+            a.sorted_pair[pos] = int32_t(p);
+        }
+        a.pair_pos[p] = pos;
+    }
+}
+
+template <bool CHUNKED>
 __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
     extern __shared__ int32_t sh[];          // count[E], cursor[E], slot[E], scan scratch
     int32_t* count = sh;
@@ -113,31 +160,35 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
 #pragma unroll
     for (int i = 0; i < kKept; ++i) {
         const uint32_t p = tid + 1024u * i;
-        kept[i] = p < pairs ? a.topk_ids[p] : -1;
+        kept[i] = (!CHUNKED && p < pairs) ? a.topk_ids[p] : -1;
+    }
+    if (CHUNKED) {
+        // the chunks' counts, added up per expert; each is replaced by the sum of the chunks before it
+        for (uint32_t e = tid; e < a.E; e += 1024) {
+            int32_t run = 0;
+            for (uint32_t c = 0; c < a.n_chunks; ++c) {
+                const int32_t v = a.chunk_count[size_t(c) * a.E + e];
+                a.chunk_count[size_t(c) * a.E + e] = run;
+                run += v;
+            }
+            count[e] = run;
+        }
     }
     __syncthreads();
     // a thread's first kKept pairs stay in registers for the scatter at the end (expert, or -1 for a pair
     // that is skipped); batches with more pairs per thread read the rest again
-    auto classify = [&](int32_t e, bool report) {
-        if (e < 0 || uint32_t(e) >= a.E) {
-            if (report) atomicOr(a.error_word, 2u);
-            return -1;
-        }
-        if (slot_of[e] < 0) {
-            if (report && !(a.flags & 2u)) atomicOr(a.error_word, 2u);
-            return -1;
-        }
-        return e;
-    };
+    auto classify = [&](int32_t e, bool report) { return route_classify(a, e, slot_of, report); };
+    if (!CHUNKED) {
 #pragma unroll
-    for (int i = 0; i < kKept; ++i) {
-        const uint32_t p = tid + 1024u * i;
-        kept[i] = p < pairs ? classify(kept[i], true) : -1;
-        if (kept[i] >= 0) atomicAdd(&count[kept[i]], 1);
-    }
-    for (uint32_t p = tid + 1024u * kKept; p < pairs; p += 1024) {
-        const int32_t e = classify(a.topk_ids[p], true);
-        if (e >= 0) atomicAdd(&count[e], 1);
+        for (int i = 0; i < kKept; ++i) {
+            const uint32_t p = tid + 1024u * i;
+            kept[i] = p < pairs ? classify(kept[i], true) : -1;
+            if (kept[i] >= 0) atomicAdd(&count[kept[i]], 1);
+        }
+        for (uint32_t p = tid + 1024u * kKept; p < pairs; p += 1024) {
+            const int32_t e = classify(a.topk_ids[p], true);
+            if (e >= 0) atomicAdd(&count[e], 1);
+        }
     }
     __syncthreads();
     // Tiles per class over all experts, needed before the tiles of the first 1024 experts can be numbered.  With one
@@ -199,6 +250,7 @@ __global__ __launch_bounds__(1024) void route_sort_kernel(FfnArgs a) {
         a.expert_offset[a.E] = row_base;
         a.n_tiles[0] = min(n_tiles, int32_t(a.tiles_cap));
     }
+    if (CHUNKED) return;                     // route_scatter_kernel puts the pairs in place
     __syncthreads();
     auto place = [&](uint32_t p, int32_t e) {
         int32_t pos = -1;
@@ -1599,7 +1651,13 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
     auto mark = [&](int kind, int begin) { if (hook) hook(user, kind, begin, stream); };
     const size_t sh = (3 * size_t(a.E) + 1024) * sizeof(int32_t);
     mark(1, 1);
-    hipLaunchKernelGGL(route_sort_kernel, dim3(1), dim3(1024), sh, stream, a);
+    if (a.n_chunks) {
+        hipLaunchKernelGGL(route_count_kernel, dim3(a.n_chunks), dim3(1024), size_t(a.E) * sizeof(int32_t), stream, a);
+        hipLaunchKernelGGL(route_sort_kernel<true>, dim3(1), dim3(1024), sh, stream, a);
+        hipLaunchKernelGGL(route_scatter_kernel, dim3(a.n_chunks), dim3(1024), size_t(a.E) * sizeof(int32_t), stream, a);
+    } else {
+        hipLaunchKernelGGL(route_sort_kernel<false>, dim3(1), dim3(1024), sh, stream, a);
+    }
     mark(1, 0);
     const uint32_t strips1 = (a.F + kStrip - 1) / kStrip;
     const uint32_t strips2 = (a.H + kStrip - 1) / kStrip;

@@ -53,9 +53,9 @@ struct StageHalf {
 };
 
 struct FfnPlan {
-    uint32_t m_tile, ksplit, pairs_cap, tiles_cap;
+    uint32_t m_tile, ksplit, pairs_cap, tiles_cap, n_chunks;
     uint64_t bytes;
-    uint64_t off_count, off_offset, off_sorted, off_pos, off_tile, off_ntiles, off_h, off_y;
+    uint64_t off_count, off_offset, off_sorted, off_pos, off_tile, off_ntiles, off_chunk, off_h, off_y;
 };
 
 inline uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
@@ -207,6 +207,8 @@ FfnPlan plan_ffn(const FfnShape& c, uint32_t T, uint32_t K) {
     p.off_pos = take(uint64_t(p.pairs_cap) * 4);
     p.off_tile = take(uint64_t(p.tiles_cap) * 16);
     p.off_ntiles = take(4);
+    p.n_chunks = pairs > kRouteChunkThreshold ? uint32_t((pairs + kRouteChunkPairs - 1) / kRouteChunkPairs) : 0u;
+    p.off_chunk = take(uint64_t(p.n_chunks) * E * 4);
     p.off_h = take(uint64_t(p.pairs_cap) * F * 2);
     p.off_y = take(uint64_t(p.ksplit) * p.pairs_cap * H * 4);
     p.bytes = o;
@@ -1074,6 +1076,8 @@ static int expert_ffn_enqueue(fluxmoe_ctx* c, uint32_t layer, const uint16_t* to
     a.pair_pos = reinterpret_cast<int32_t*>(w + p.off_pos);
     a.tile_rec = reinterpret_cast<int4*>(w + p.off_tile);
     a.n_tiles = reinterpret_cast<int32_t*>(w + p.off_ntiles);
+    a.chunk_count = reinterpret_cast<int32_t*>(w + p.off_chunk);
+    a.n_chunks = p.n_chunks;
     a.hbuf = reinterpret_cast<uint16_t*>(w + p.off_h);
     a.ybuf = reinterpret_cast<float*>(w + p.off_y);
     a.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);
@@ -1161,6 +1165,8 @@ int fluxmoe_shared_expert_ffn(fluxmoe_ctx* c, const uint16_t* w13, const uint16_
     a.pair_pos = reinterpret_cast<int32_t*>(w + p.off_pos);
     a.tile_rec = reinterpret_cast<int4*>(w + p.off_tile);
     a.n_tiles = reinterpret_cast<int32_t*>(w + p.off_ntiles);
+    a.chunk_count = reinterpret_cast<int32_t*>(w + p.off_chunk);
+    a.n_chunks = p.n_chunks;
     a.hbuf = reinterpret_cast<uint16_t*>(w + p.off_h);
     a.ybuf = reinterpret_cast<float*>(w + p.off_y);
     a.error_word = reinterpret_cast<uint32_t*>(c->ws + c->err_off);

@@ -27,6 +27,9 @@ struct FfnArgs {
     int32_t* pair_pos;           // [pairs_cap]  position of a pair in sorted order, -1 = skipped
     int4* tile_rec;              // [tiles_cap]  (expert, first sorted row, rows, slot); rows = 0 past the last tile
     int32_t* n_tiles;            // [1]
+    int32_t* chunk_count;        // [n_chunks][E]  large batches: pairs per (chunk of kRouteChunkPairs pairs, expert),
+                                 // turned into the chunk's first position inside the expert's rows by the grouping kernel
+    uint32_t n_chunks;           // 0: the grouping kernel counts and scatters the pairs itself (one workgroup)
     uint16_t* hbuf;              // BF16 [pairs_cap][F]
     float* ybuf;                 // FP32 [ksplit][pairs_cap][H]
     uint32_t* error_word;
@@ -40,6 +43,11 @@ struct FfnArgs {
     uint32_t tiled_group;        // super-rows of the LDS-direct gate/up kernel that share a column block in time;
                                  // 0 = launch_ffn derives it from the rows per expert
 };
+
+// Batches with more pairs than this are counted and scattered by one workgroup per kRouteChunkPairs pairs
+// around the single workgroup that scans the experts (a single workgroup needs 0.4 ms for 330000 pairs).
+constexpr uint32_t kRouteChunkThreshold = 32768;
+constexpr uint32_t kRouteChunkPairs = 8192;
 
 // hook(user, kind, begin, stream) is called around every kernel when timing is on
 // (kinds: 1 grouping, 2 gate/up product + SwiGLU, 3 down product, 4 combine)

@@ -114,6 +114,16 @@ def test_more_experts_than_one_round_of_the_grouping_scans():
                                hidden=64, ffn=128, routing="uniform"), seed=3)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(tokens=20000, top_k=2, n_experts=1500, n_slots=1500, hidden=64, ffn=128, routing="uniform"),   # strip kernels, two scan rounds
+    dict(tokens=33000, top_k=1, n_experts=4, n_slots=4, hidden=64, ffn=128),                            # LDS-tiled kernels
+])
+def test_batches_grouped_by_several_workgroups(kw):
+    """More than 32768 pairs are counted and put in place by one workgroup per 8192 pairs around the
+    workgroup that scans the experts; smaller batches by that workgroup alone."""
+    run_ffn_case(inputs.scaled(inputs.CONFIGS["c1_tiny"], **kw), seed=7)
+
+
 def test_all_pairs_on_one_expert_and_tiles_of_every_size_class():
     """Degenerate routings of the tile list: every token on expert 3 (two full 128-row tiles and a 44-row
     one with the strip kernels' largest tile forced), and expert row counts 1, 17, 33, 65, 97, 128, 129 that
