@@ -73,6 +73,17 @@ def test_ragged_shapes_single_group_tail():
     run_against_model(cfg, [(0, [1, 0], [3, 1])])
 
 
+@pytest.mark.parametrize("waves,blocks_per_wave", [(4, 1), (4, 6), (8, 1), (16, 2), (16, 7)])
+def test_launch_shape_overrides_of_the_decode_kernel(monkeypatch, waves, blocks_per_wave):
+    """Workgroups of 4, 8 or 16 wavefronts and other block counts per wavefront (read at context creation)
+    must place the same bits: enough blocks for several workgroups of each shape, tensors that end inside a
+    wavefront's stride, two layers so that a call evicts another layer's experts."""
+    monkeypatch.setenv("FLUXMOE_DECODE_WAVES", str(waves))
+    monkeypatch.setenv("FLUXMOE_DECODE_BLOCKS_PER_WAVE", str(blocks_per_wave))
+    cfg = inputs.scaled(inputs.CONFIGS["c1_tiny"], n_experts=5, hidden=328, ffn=456, n_slots=4, n_layers=2)
+    run_against_model(cfg, [(0, [3, 0, 4], [1, 3, 0]), (1, [2, 1], [3, 2]), (0, [1], [0])])
+
+
 def test_adversarial_bit_patterns():
     """NaN/Inf/zero/subnormal words, a single exponent, all 256 exponents, codes at the length
     limit: the decoder must still return the exact bits."""
