@@ -1564,6 +1564,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_d2l_kernel(FfnArgs a) {
 }
 
 // out[t][:] (+)= sum_k gate * sum_split y
+template <uint32_t kGroup>
 __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
     const uint32_t tok = blockIdx.y;
     const uint32_t h = (blockIdx.x * 256 + threadIdx.x) * 4;
@@ -1571,10 +1572,11 @@ __global__ __launch_bounds__(256) void combine_kernel(FfnArgs a) {
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     float* o = a.out + size_t(tok) * a.H + h;
     if (a.flags & 1u) s = *reinterpret_cast<const float4*>(o);
-    // Eight pairs of the token at a time: their positions and gates are fetched together, then their rows of
-    // y, so that the loads overlap instead of following each other pair by pair.  A skipped pair reads row 0
-    // (a cache hit) and adds nothing; the sums run over the splits and then over k, in that order.
-    constexpr uint32_t kGroup = 8;
+    // kGroup pairs of the token at a time (the launcher takes the smallest of 2, 4, 8, 16 that covers top-k,
+    // 16 beyond): their positions and gates are fetched together, then their rows of y, so that the loads
+    // overlap instead of following each other pair by pair.  A skipped pair, and a place of the group past
+    // top-k, reads row 0 (a cache hit) and adds nothing; the sums run over the splits and then over k, in that
+    // order, whatever the group size.
     for (uint32_t k0 = 0; k0 < a.K; k0 += kGroup) {
         int32_t pos[kGroup];
         float gate[kGroup];
@@ -1659,6 +1661,12 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
         hipLaunchKernelGGL(route_sort_kernel<false>, dim3(1), dim3(1024), sh, stream, a);
     }
     mark(1, 0);
+    auto launch_combine = [&](dim3 grid) {
+        if (a.K <= 2) hipLaunchKernelGGL(combine_kernel<2>, grid, dim3(256), 0, stream, a);
+        else if (a.K <= 4) hipLaunchKernelGGL(combine_kernel<4>, grid, dim3(256), 0, stream, a);
+        else if (a.K <= 8) hipLaunchKernelGGL(combine_kernel<8>, grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL(combine_kernel<16>, grid, dim3(256), 0, stream, a);
+    };
     const uint32_t strips1 = (a.F + kStrip - 1) / kStrip;
     const uint32_t strips2 = (a.H + kStrip - 1) / kStrip;
     const dim3 g1((strips1 + 1) / 2, a.tiles_cap, 1);
@@ -1759,7 +1767,7 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
         mark(3, 0);
         const dim3 gc2((a.H / 4 + 255) / 256, a.T, 1);
         mark(4, 1);
-        hipLaunchKernelGGL(combine_kernel, gc2, dim3(256), 0, stream, a);
+        launch_combine(gc2);
         mark(4, 0);
         return hipGetLastError();
     }
@@ -1782,7 +1790,7 @@ hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHo
     mark(3, 0);
     const dim3 gc((a.H / 4 + 255) / 256, a.T, 1);
     mark(4, 1);
-    hipLaunchKernelGGL(combine_kernel, gc, dim3(256), 0, stream, a);
+    launch_combine(gc);
     mark(4, 0);
     return hipGetLastError();
 }
