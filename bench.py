@@ -184,6 +184,7 @@ def main():
 
     ms_per_step = elapsed / args.steps * 1e3
     n_launch = len(waves)                                    # decode launches per step
+    pattern_probe = access_pattern_probe(comp_blocks // n_launch, dense_bytes / comp_blocks)
     decode_ms = prof["decode"][0] / max(1, prof["decode"][1])            # mean launch
     decode_step_ms = decode_ms * n_launch
     ffn_ms = sum(prof[k][0] for k in ("grouping", "gemm1_swiglu", "gemm2", "combine")) / n_break
@@ -239,6 +240,9 @@ def main():
     }
     if copy_gbps is not None:
         result["device_copy_GBps"] = copy_gbps                # read + write bytes of plain copies
+    if pattern_probe is not None:
+        pattern_probe["decode_over_probe"] = round(achieved / pattern_probe["GBps"], 4)
+        result["decode_access_pattern_probe"] = pattern_probe
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(pool, cfg, blob, w13, w2, args.cpu_seconds)
@@ -248,6 +252,36 @@ def main():
             result["cpu_baseline"]["expert_ffn"] = {"error": str(exc)[:200]}
     print(json.dumps(result), flush=True)
     pool.close()
+
+
+def access_pattern_probe(n_blocks, out_bytes_per_block, reps=5):
+    """What HBM gives the decode kernel's access pattern on this machine: a kernel of the same launch shape that
+    reads n_blocks blocks of 4 KiB, one per wavefront, and writes out_bytes_per_block (on average) for each in
+    1 KiB pieces, with nothing in between (fluxmoe_stream_mix).  Untimed leg, after the timed steps."""
+    import torch
+    from paper_2604_02715_amd import binding as B
+    small = max(128, int(round((out_bytes_per_block - 48) / 128.0)) * 128)   # three blocks of eight write 128 more
+    waves = int(os.environ.get("FLUXMOE_DECODE_WAVES", "8"))
+    per_wave = int(os.environ.get("FLUXMOE_DECODE_BLOCKS_PER_WAVE", "3"))
+    if n_blocks < 1 or waves not in (4, 8, 16) or not 1 <= per_wave <= 1024:
+        return None
+    src = torch.empty(n_blocks * 4096, dtype=torch.uint8, device="cuda").random_(0, 256)
+    dst = torch.empty(n_blocks * (small + 128), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    run = lambda: B.fluxmoe_stream_mix(dst.data_ptr(), dst.numel(), src.data_ptr(), src.numel(), small, waves,
+                                       per_wave, 0, stream)
+    written = run()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(reps):
+        run()
+    ev1.record()
+    torch.cuda.synchronize()
+    ms = ev0.elapsed_time(ev1) / reps
+    return {"GBps": round((src.numel() + written) / (ms * 1e-3) / 1e9, 1), "ms": round(ms, 4),
+            "bytes_read": src.numel(), "bytes_written": written,
+            "what": "fluxmoe_stream_mix: the decode launch's shape, loads and stores without the decoding"}
 
 
 def decode_kernel_source_hash():

@@ -459,6 +459,26 @@ int fluxmoe_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_w
                         void* stream);
 
 /*
+ * Measurement aid: the memory traffic of the materialization kernel without its work, in the same
+ * launch shape (workgroups of waves_per_workgroup = 4, 8 or 16 wavefronts, blocks_per_wave blocks to
+ * each wavefront; order 0 deals the blocks round-robin over all wavefronts of the launch as the
+ * materialization kernel does, order 1 gives a workgroup consecutive blocks which its wavefronts
+ * pass over side by side, order 2 gives every wavefront consecutive blocks).  `src` (device, 128-byte aligned) is read
+ * as src_bytes / 4096 blocks of 4096 bytes, each by one wavefront with streaming 16-byte loads;
+ * for every block the wavefront then writes out_bytes_small bytes (three blocks of every eight:
+ * out_bytes_small + 128; a multiple of 128 in [128, 16384]) to `dst` (device, 128-byte aligned),
+ * block after block without gaps, in pieces of 1 KiB with streaming 16-byte stores whose data
+ * depend on the loads.  *bytes_written (may be NULL) receives the bytes written; FLUXMOE_EINVAL
+ * if dst_bytes is less than that, nothing is enqueued then.  Timed by the caller with the ratio
+ * of a pool (4096 / out bytes = compressed / dense), it gives what HBM delivers to this access
+ * pattern on the box: the ceiling of the decode kernel short of changing the container.
+ * Needs no context.
+ */
+int fluxmoe_stream_mix(void* dst, uint64_t dst_bytes, const void* src, uint64_t src_bytes,
+                       uint32_t out_bytes_small, uint32_t waves_per_workgroup, uint32_t blocks_per_wave,
+                       uint32_t order, uint64_t* bytes_written, void* stream);
+
+/*
  * Measurement aid: n_workgroups workgroups of four wavefronts each issue iters x 16 independent
  * v_mfma_f32_32x32x16_bf16 (32768 flops each) on operands taken once from `operands` (device, 64 KiB
  * of BF16 values, 16-byte aligned) and no memory traffic in the loop; `out` (device, n_workgroups *

@@ -105,6 +105,8 @@ EXPORTS = {
     "fluxmoe_shared_expert_ffn": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                             C.c_void_p, C.c_uint32, C.c_void_p]),
     "fluxmoe_stream_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint32, C.c_void_p]),
+    "fluxmoe_stream_mix": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32,
+                                     C.c_uint32, C.c_uint32, C.POINTER(C.c_uint64), C.c_void_p]),
     "fluxmoe_mfma_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p]),
     "fluxmoe_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "fluxmoe_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_uint32)]),
@@ -286,6 +288,15 @@ def fluxmoe_shared_expert_ffn(ctx, w13_ptr, w2_ptr, tokens_ptr, T, out_ptr, flag
 
 def fluxmoe_stream_copy(dst_ptr, src_ptr, nbytes, n_workgroups, stream=None):
     _check(lib().fluxmoe_stream_copy(dst_ptr, src_ptr, nbytes, n_workgroups, stream))
+
+
+def fluxmoe_stream_mix(dst_ptr, dst_bytes, src_ptr, src_bytes, out_bytes_small, waves_per_workgroup=8,
+                       blocks_per_wave=3, order=0, stream=None):
+    """Returns the bytes written."""
+    written = C.c_uint64(0)
+    _check(lib().fluxmoe_stream_mix(dst_ptr, dst_bytes, src_ptr, src_bytes, out_bytes_small, waves_per_workgroup,
+                                    blocks_per_wave, order, C.byref(written), stream))
+    return int(written.value)
 
 
 def fluxmoe_mfma_probe(operands_ptr, out_ptr, n_workgroups, iters, stream=None):

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libfluxmoe.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
-SOURCES = ["encoder.cpp", "planner.cpp", "fluxmoe_api.hip", "decode_kernel.hip", "ffn_kernels.hip", "paged_tensor.hip"]
+SOURCES = ["encoder.cpp", "planner.cpp", "fluxmoe_api.hip", "decode_kernel.hip", "ffn_kernels.hip", "paged_tensor.hip", "probe_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

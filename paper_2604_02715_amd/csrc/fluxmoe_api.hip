@@ -1186,6 +1186,32 @@ int fluxmoe_stream_copy(void* dst, const void* src, uint64_t bytes, uint32_t n_w
     return FLUXMOE_OK;
 }
 
+int fluxmoe_stream_mix(void* dst, uint64_t dst_bytes, const void* src, uint64_t src_bytes, uint32_t out_bytes_small,
+                       uint32_t waves_per_workgroup, uint32_t blocks_per_wave, uint32_t order, uint64_t* bytes_written,
+                       void* stream) {
+    if (!dst || !src) return set_error(FLUXMOE_EINVAL, "NULL argument");
+    if ((uintptr_t(dst) | uintptr_t(src)) & 127) return set_error(FLUXMOE_EINVAL, "128-byte alignment required");
+    if (out_bytes_small < 128 || out_bytes_small > 16384 || out_bytes_small % 128)
+        return set_error(FLUXMOE_EINVAL, "out_bytes_small must be a multiple of 128 in [128, 16384]");
+    if (waves_per_workgroup != 4 && waves_per_workgroup != 8 && waves_per_workgroup != 16)
+        return set_error(FLUXMOE_EINVAL, "waves_per_workgroup must be 4, 8 or 16");
+    if (blocks_per_wave == 0 || blocks_per_wave > 1024) return set_error(FLUXMOE_EINVAL, "bad blocks_per_wave");
+    if (order > 2) return set_error(FLUXMOE_EINVAL, "order must be 0, 1 or 2");
+    const uint64_t n_blocks = src_bytes / 4096;
+    if (n_blocks == 0 || n_blocks > (1ull << 30)) return set_error(FLUXMOE_EINVAL, "src must hold 1 to 2^30 blocks of 4096 bytes");
+    const uint64_t need = stream_mix_out_bytes(n_blocks, out_bytes_small);
+    if (dst_bytes < need)
+        return set_error(FLUXMOE_EINVAL, "dst holds %llu bytes, %llu blocks write %llu", (unsigned long long)dst_bytes,
+                         (unsigned long long)n_blocks, (unsigned long long)need);
+    const uint64_t per_wg = uint64_t(waves_per_workgroup) * blocks_per_wave;
+    const uint64_t n_wg = (n_blocks + per_wg - 1) / per_wg;
+    if (n_wg > (1u << 24)) return set_error(FLUXMOE_EINVAL, "too many workgroups (%llu)", (unsigned long long)n_wg);
+    HIPCHECK(launch_stream_mix(dst, src, uint32_t(n_blocks), out_bytes_small, int(waves_per_workgroup), blocks_per_wave,
+                               order, uint32_t(n_wg), static_cast<hipStream_t>(stream)));
+    if (bytes_written) *bytes_written = need;
+    return FLUXMOE_OK;
+}
+
 int fluxmoe_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, uint32_t iters, void* stream) {
     if (!operands || !out) return set_error(FLUXMOE_EINVAL, "NULL argument");
     if ((uintptr_t(operands) & 15) || (uintptr_t(out) & 3)) return set_error(FLUXMOE_EINVAL, "operands must be 16-byte aligned");

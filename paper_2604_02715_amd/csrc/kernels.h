@@ -55,5 +55,10 @@ typedef void (*SpanHook)(void* user, int kind, int begin, hipStream_t stream);
 hipError_t launch_ffn(const FfnArgs& args, int n_cus, hipStream_t stream, SpanHook hook, void* user);
 hipError_t launch_mfma_probe(const void* operands, float* out, uint32_t n_workgroups, uint32_t iters,
                              hipStream_t stream);
+// The decode kernel's launch shape and memory accesses without its work (probe_kernels.hip): n_blocks blocks of
+// 4096 bytes read, stream_mix_out_bytes(n_blocks, small) bytes written (small or small + 128 bytes per block).
+uint64_t stream_mix_out_bytes(uint64_t n_blocks, uint32_t small);
+hipError_t launch_stream_mix(void* dst, const void* src, uint32_t n_blocks, uint32_t small, int waves_per_wg,
+                             uint32_t per_wave, uint32_t order, uint32_t n_workgroups, hipStream_t stream);
 
 }  // namespace fluxmoe
